@@ -1,0 +1,216 @@
+"""CPU oracle for the SERQ online linear layer.  TEST INFRASTRUCTURE ONLY.
+
+Nothing in the product path may import this file: it exists so that the tests,
+the smoke check and the benchmark's CPU-baseline leg have an independent, slow,
+obviously-correct statement of what the HIP kernels must compute.  It shares no
+code, table or helper with the HIP path.
+
+Everything here is the plain definition written out with NumPy:
+
+  * quantisation scale and integer codes are taken in IEEE fp32 (the precision
+    the kernels use for the same decision), with round-half-to-even;
+  * the integer GEMM is exact;
+  * the dequantising epilogue and the rank-r compensation are evaluated in fp64.
+
+Notation follows the paper: X activations [tokens M, input channels K],
+W weights stored [output channels N, input channels K] (so a "weight row" of
+the paper, one input channel, is a column here), s the static flattening
+vector, P the saliency permutation, R the single compensation matrix [r, N].
+
+Pins (tests/test_oracle_*.py): hand-worked tiny layer, the integer-layer
+reduction to a textbook matmul, the scale/2 rounding bound, permutation and
+flattening invariances, the r = 0 reduction, and the exact-residual identity
+main + compensation == Q(X) . [W_s ; deq(Q(W_r))].  No function is unpinned.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F32 = np.float32
+
+
+def qmax(bits: int) -> int:
+    """Largest code of a symmetric n-bit grid, 2^(n-1) - 1 (Sec. 2.1, Eq. 1).
+
+    The printed clip range "[-2^(n-1)-1, 2^(n-1)-1]" is read as the symmetric
+    range [-(2^(n-1)-1), +(2^(n-1)-1)], the one consistent with the scale
+    max|X| / (2^(n-1)-1) given in the same equation.
+    """
+    return (1 << (bits - 1)) - 1
+
+
+def flatten(X: np.ndarray, s_inv) -> np.ndarray:
+    """X~ = X . diag(s^-1), one fp32 multiply per element (Sec. 3.2, Eq. 4).
+
+    `s_inv` is the reciprocal vector prepared offline (see pack_weights);
+    None means the activations arrive already flattened.
+    """
+    X = np.asarray(X, dtype=F32)
+    if s_inv is None:
+        return X
+    return X * np.asarray(s_inv, dtype=F32)[None, :]
+
+
+def quantize_act(X: np.ndarray, s_inv, abits: int):
+    """Per-token symmetric max-scaled quantisation of the flattened activations (Eq. 1).
+
+    scale[m] = max_k |v[m,k]| / qmax   (fp32 division; 1.0 for an all-zero token)
+    Xq[m,k]  = clip(rne(v[m,k] / scale[m]), -qmax, +qmax)
+    Returns (Xq int8 [M,K], scale fp32 [M]).
+    """
+    v = flatten(X, s_inv)
+    q = F32(qmax(abits))
+    amax = np.max(np.abs(v), axis=1).astype(F32) if v.shape[1] else np.zeros(v.shape[0], F32)
+    scale = np.where(amax > 0, amax / q, F32(1.0)).astype(F32)
+    t = (v / scale[:, None]).astype(F32)
+    Xq = np.clip(np.rint(t), -q, q).astype(np.int8)
+    return Xq, scale
+
+
+def saliency_permutation(Wt: np.ndarray) -> np.ndarray:
+    """Descending-saliency order P of the input channels (Sec. 3.2, text before Eq. 5).
+
+    After flattening, the salient weight rows (input channels) are recognised
+    by their scale; the scale of channel k is taken as max_n |W~[n,k]|.  Ties
+    keep the lower original index first.  perm[kp] = original channel at
+    permuted position kp.
+    """
+    sal = np.max(np.abs(Wt), axis=0) if Wt.shape[0] else np.zeros(Wt.shape[1], F32)
+    return np.argsort(-sal.astype(F32), kind="stable").astype(np.int32)
+
+
+def pack_weights(W: np.ndarray, s, r: int, perm=None):
+    """Offline preparation of one layer (Eq. 4, Eq. 5; per-output-channel Eq. 1).
+
+    W [N,K] fp32 (exactly widened storage values), s [K] fp32 or None.
+      W~[n,k]   = W[n,k] * s[k]                       (fp32)
+      W^        = W~[:, perm]                         (salient channels lead)
+      wscale[n] = max_k |W^[n,k]| / 7                 (fp32; 1.0 for a zero row)
+      Wq[n,k]   = clip(rne(W^[n,k] / wscale[n]), -7, 7)
+      R[j,n]    = W^[n,j] - wscale[n] * Wq[n,j],  j < r   (fp64, exact residual)
+      s_inv[kp] = 1 / s[perm[kp]]                     (fp32; what quantize_act multiplies by)
+    Returns dict(Wq int8 [N,K], wscale fp32 [N], perm int32 [K], s_inv fp32 [K], R fp64 [r,N]).
+    """
+    W = np.asarray(W, dtype=F32)
+    N, K = W.shape
+    s = np.ones(K, F32) if s is None else np.asarray(s, dtype=F32)
+    Wt = W * s[None, :]
+    perm = saliency_permutation(Wt) if perm is None else np.asarray(perm, dtype=np.int32)
+    assert sorted(perm.tolist()) == list(range(K)), "perm must be a permutation of the channels"
+    Wp = Wt[:, perm]
+    amax = np.max(np.abs(Wp), axis=1).astype(F32)
+    wscale = np.where(amax > 0, amax / F32(7), F32(1.0)).astype(F32)
+    Wq = np.clip(np.rint((Wp / wscale[:, None]).astype(F32)), -7, 7).astype(np.int8)
+    R = (Wp[:, :r].astype(np.float64)
+         - wscale.astype(np.float64)[:, None] * Wq[:, :r].astype(np.float64)).T.copy()
+    s_inv = (F32(1.0) / s)[perm].astype(F32)
+    return {"Wq": Wq, "wscale": wscale, "perm": perm, "s_inv": s_inv, "R": R}
+
+
+def gemm_i32(Xq: np.ndarray, Wq: np.ndarray) -> np.ndarray:
+    """acc[m,n] = sum_k Xq[m,k] * Wq[n,k], exact (Eq. 2; first term of Eq. 7).
+
+    The contraction is done by a float64 matrix product: every operand is an
+    integer of at most 8 bits and every partial sum stays far below 2^53, so
+    the result is the exact integer whatever the summation order.
+    """
+    M, K = Xq.shape
+    bound = 128.0 * 128.0 * max(K, 1)
+    assert bound < 2.0 ** 31
+    acc = Xq.astype(np.float64) @ Wq.astype(np.float64).T
+    return acc.astype(np.int64).astype(np.int32)
+
+
+def gemm_i32_loops(Xq: np.ndarray, Wq: np.ndarray) -> np.ndarray:
+    """The same sum as gemm_i32 as three nested Python loops (tiny inputs only)."""
+    M, K = Xq.shape
+    N = Wq.shape[0]
+    acc = np.zeros((M, N), dtype=np.int64)
+    for m in range(M):
+        for n in range(N):
+            t = 0
+            for k in range(K):
+                t += int(Xq[m, k]) * int(Wq[n, k])
+            acc[m, n] = t
+    return acc.astype(np.int32)
+
+
+def lowrank(Xq: np.ndarray, R: np.ndarray, s_begin: int = 0) -> np.ndarray:
+    """lr[m,n] = sum_{j<r} Xq[m, s_begin+j] * R[j,n]  in fp64 (second term of Eq. 7).
+
+    Only the salient channel block S = [s_begin, s_begin+r) of the *quantised*
+    activations takes part; the common factor scale[m] is applied in `linear`.
+    """
+    r = 0 if R is None else R.shape[0]
+    if r == 0:
+        return np.zeros((Xq.shape[0], 0 if R is None else R.shape[1]), np.float64)
+    return Xq[:, s_begin:s_begin + r].astype(np.float64) @ np.asarray(R, dtype=np.float64)
+
+
+def linear(Xq, scale, Wq, wscale, R=None, s_begin: int = 0, acc=None) -> np.ndarray:
+    """Y[m,n] = scale[m] * ( wscale[n] * acc[m,n] + lr[m,n] )  in fp64 (Eq. 2 + Eq. 7).
+
+    `R` holds the values actually stored (fp16/bf16 widened exactly) or None / r = 0
+    for the plain W4A4 / W4A8 GEMM.  `acc` may be passed in to reuse a GEMM.
+    """
+    if acc is None:
+        acc = gemm_i32(Xq, Wq)
+    y = np.asarray(wscale, np.float64)[None, :] * acc.astype(np.float64)
+    if R is not None and R.shape[0] > 0:
+        y = y + lowrank(Xq, R, s_begin)
+    return np.asarray(scale, np.float64)[:, None] * y
+
+
+def linear_f32(Xq, scale, Wq, wscale, R=None, s_begin: int = 0, acc=None) -> np.ndarray:
+    """The same formula evaluated in fp32 in the stated order (documents fp32's share of the tolerance)."""
+    if acc is None:
+        acc = gemm_i32(Xq, Wq)
+    y = np.asarray(wscale, F32)[None, :] * acc.astype(F32)
+    if R is not None and R.shape[0] > 0:
+        r = R.shape[0]
+        y = y + (Xq[:, s_begin:s_begin + r].astype(F32) @ np.asarray(R, dtype=F32)).astype(F32)
+    return (np.asarray(scale, F32)[:, None] * y).astype(F32)
+
+
+def dequant_reference(X, s, W, r: int, abits: int, perm=None):
+    """Convenience: the whole layer from unquantised inputs, with the exact residual R.
+
+    Returns (Y fp64, pieces dict).  Used by the tests that check the
+    compensation really reduces the error of the salient channels.
+    """
+    pk = pack_weights(W, s, r, perm)
+    Xp = np.asarray(X, dtype=F32)[:, pk["perm"]]
+    Xq, scale = quantize_act(Xp, pk["s_inv"], abits)
+    Y = linear(Xq, scale, pk["Wq"], pk["wscale"], pk["R"] if r > 0 else None)
+    pk.update({"Xq": Xq, "scale": scale})
+    return Y, pk
+
+
+def rel_errors(Y, Y64):
+    """The two error measures the parity tests use for Y.
+
+    global : max |Y - Y64| / max |Y64|
+    mixed  : max over elements of |Y - Y64| / (|Y64| + rms(Y64))
+    """
+    Y = np.asarray(Y, np.float64)
+    d = np.abs(Y - Y64)
+    denom = float(np.max(np.abs(Y64))) if Y64.size else 1.0
+    rms = float(np.sqrt(np.mean(Y64 * Y64))) if Y64.size else 1.0
+    g = float(np.max(d)) / denom if Y64.size and denom > 0 else 0.0
+    mix = float(np.max(d / (np.abs(Y64) + rms))) if Y64.size and rms > 0 else 0.0
+    return g, mix
+
+
+def effective_weight_bits(K: int, N: int, r: int, group: int = 0, scale_bits: int = 16,
+                          r_bits: int = 4) -> float:
+    """Stored bits per main-weight element for one layer (Tables 1-2, effective bit-width).
+
+    4-bit codes, one `scale_bits` scale per group of `group` input channels
+    (group = 0: one per output channel), plus an r x N compensation matrix of
+    `r_bits`-bit codes.
+    """
+    n_w = K * N
+    bits = 4.0 * n_w
+    bits += scale_bits * (N * (K // group) if group else N)
+    bits += r_bits * r * N
+    return bits / n_w

@@ -1,0 +1,244 @@
+"""Pins for the CPU oracle: every check here compares it with something other than itself.
+
+Hand-worked numbers (tests/golden/tiny_layer.txt), textbook integer matmul,
+the rounding bound of Eq. 1, the exact identities of Eq. 4 / Eq. 6, the r = 0
+reduction (Eq. 2), and the exact-residual identity behind Eq. 5 + Eq. 7.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import workloads
+from oracle import serq_oracle as orc
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def _read_golden(path):
+    out = {}
+    with open(path) as f:
+        lines = [ln.strip() for ln in f if ln.strip() and not ln.startswith("#")]
+    i = 0
+    while i < len(lines):
+        name, rows, cols = lines[i].split()
+        rows, cols = int(rows), int(cols)
+        data = [[float(t) for t in lines[i + 1 + r].split()] for r in range(rows)]
+        arr = np.array(data, dtype=np.float64)
+        assert arr.shape == (rows, cols)
+        out[name] = arr
+        i += 1 + rows
+    return out
+
+
+def test_T1_hand_worked_tiny_layer():
+    g = _read_golden(os.path.join(HERE, "golden", "tiny_layer.txt"))
+    X, W, s = g["X"].astype(np.float32), g["W"].astype(np.float32), g["s"][0].astype(np.float32)
+    pk = orc.pack_weights(W, s, r=2)
+    assert pk["perm"].tolist() == g["perm"][0].astype(int).tolist()
+    assert np.array_equal(pk["s_inv"], g["s_inv"][0].astype(np.float32))
+    assert np.array_equal(pk["wscale"], g["wscale"][0].astype(np.float32))
+    assert np.array_equal(pk["Wq"], g["Wq"].astype(np.int8))
+    assert np.array_equal(pk["R"], g["R"])
+    Xp = X[:, pk["perm"]]
+    Xq, scale = orc.quantize_act(Xp, pk["s_inv"], 4)
+    assert np.array_equal(scale, g["scale"][0].astype(np.float32))
+    assert np.array_equal(Xq, g["Xq"].astype(np.int8))
+    acc = orc.gemm_i32(Xq, pk["Wq"])
+    assert np.array_equal(acc, g["acc"].astype(np.int32))
+    assert np.array_equal(orc.gemm_i32_loops(Xq, pk["Wq"]), g["acc"].astype(np.int32))
+    Y = orc.linear(Xq, scale, pk["Wq"], pk["wscale"], pk["R"])
+    assert np.array_equal(Y, g["Y"])
+    Yf = orc.linear_f32(Xq, scale, pk["Wq"], pk["wscale"], pk["R"])
+    assert np.array_equal(Yf.astype(np.float64), g["Y"])
+    # the one-call convenience path gives the same answer
+    Y2, _ = orc.dequant_reference(X, s, W, 2, 4)
+    assert np.array_equal(Y2, g["Y"])
+
+
+@pytest.mark.parametrize("abits", [4, 8])
+def test_T2_integer_layer_is_textbook_matmul(abits):
+    q = orc.qmax(abits)
+    X, W = workloads.integer_layer(M=9, K=64, N=13, qx=q, seed=7 + abits)
+    pk = orc.pack_weights(W, None, r=0, perm=np.arange(64))
+    Xq, scale = orc.quantize_act(X, None, abits)
+    assert np.all(scale == 1.0) and np.all(pk["wscale"] == 1.0)
+    assert np.array_equal(Xq.astype(np.float32), X)
+    assert np.array_equal(pk["Wq"].astype(np.float32), W)
+    want = X.astype(np.int64) @ W.astype(np.int64).T
+    assert np.array_equal(orc.gemm_i32(Xq, pk["Wq"]).astype(np.int64), want)
+    Y = orc.linear(Xq, scale, pk["Wq"], pk["wscale"])
+    assert np.array_equal(Y, want.astype(np.float64))
+
+
+def test_rounding_is_half_to_even():
+    # scale is exactly 1 (row maximum 7): codes are rne of the values themselves
+    X = np.array([[7, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 3.5, 4.5, -6.5, 6.49, -3.51]], np.float32)
+    Xq, scale = orc.quantize_act(X, None, 4)
+    assert scale[0] == 1.0
+    assert Xq[0].tolist() == [7, 0, 2, 2, 0, -2, -2, 4, 4, -6, 6, -4]
+
+
+def test_zero_token_and_zero_weight_row():
+    X = np.zeros((2, 16), np.float32)
+    X[1, 3] = -2.0
+    Xq, scale = orc.quantize_act(X, None, 8)
+    assert scale[0] == 1.0 and not Xq[0].any()
+    assert Xq[1, 3] == -127 and scale[1] == np.float32(2.0) / np.float32(127)
+    W = np.zeros((2, 16), np.float32)
+    W[0, 1] = 1.0
+    pk = orc.pack_weights(W, None, 0)
+    assert pk["wscale"][1] == 1.0 and not pk["Wq"][1].any()
+
+
+@pytest.mark.parametrize("abits", [4, 8])
+def test_T3_rounding_bound_and_extremes(abits):
+    spec = workloads.config1().with_(M=33, K=512, abits=abits)
+    L = workloads.make_layer(spec, want=("X", "s"))
+    X = L["X"].float().numpy()
+    s_inv = (np.float32(1) / L["s"].numpy()).astype(np.float32)
+    Xq, scale = orc.quantize_act(X, s_inv, abits)
+    q = orc.qmax(abits)
+    v = X.astype(np.float64) * s_inv.astype(np.float64)  # the exact product
+    v32 = (X * s_inv[None, :]).astype(np.float64)
+    assert np.max(np.abs(Xq)) <= q
+    err = np.abs(v32 - scale.astype(np.float64)[:, None] * Xq)
+    assert np.all(err <= 0.5 * scale[:, None] * (1 + 1e-6))
+    # fp32 flattening is within one rounding of the exact product
+    assert np.all(np.abs(v - v32) <= np.abs(v) * 2.0 ** -24 + 1e-300)
+    am = np.argmax(np.abs(v32), axis=1)
+    rows = np.arange(X.shape[0])
+    assert np.all(np.abs(Xq[rows, am]) == q)
+    assert np.all(np.sign(Xq[rows, am]) == np.sign(v32[rows, am]))
+    assert np.allclose(scale, np.max(np.abs(v32), axis=1) / q, rtol=1e-7)
+
+
+def test_T4_permutation_invariance():
+    spec = workloads.config1().with_(M=5, K=128, N=24, r=16)
+    L = workloads.make_layer(spec)
+    X, W, s = L["X"].float().numpy(), L["W"].float().numpy(), L["s"].numpy()
+    Y0, p0 = orc.dequant_reference(X, s, W, 16, 4)
+    rng = np.random.default_rng(5)
+    pi = rng.permutation(128)
+    # the same layer with its input channels presented in another order
+    Y1, p1 = orc.dequant_reference(X[:, pi], s[pi], W[:, pi], 16, 4)
+    assert np.array_equal(p0["scale"], p1["scale"])
+    assert np.array_equal(p0["wscale"], p1["wscale"])
+    assert np.array_equal(orc.gemm_i32(p0["Xq"], p0["Wq"]), orc.gemm_i32(p1["Xq"], p1["Wq"]))
+    # the saliency order picks the same physical channels, so S maps to itself
+    assert np.array_equal(pi[p1["perm"]][:16], p0["perm"][:16])
+    assert np.allclose(Y0, Y1, rtol=1e-12, atol=1e-12)
+    # an arbitrary (non-saliency) order of the non-salient channels changes nothing either
+    perm2 = np.concatenate([p0["perm"][:16], rng.permutation(p0["perm"][16:])])
+    Y2, p2 = orc.dequant_reference(X, s, W, 16, 4, perm=perm2)
+    assert np.array_equal(orc.gemm_i32(p0["Xq"], p0["Wq"]), orc.gemm_i32(p2["Xq"], p2["Wq"]))
+    assert np.allclose(Y0, Y2, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("abits", [4, 8])
+def test_T5_rank_zero_is_plain_quantised_gemm(abits):
+    spec = workloads.config1().with_(M=6, K=64, N=20, r=16, abits=abits)
+    L = workloads.make_layer(spec)
+    X, W, s = L["X"].float().numpy(), L["W"].float().numpy(), L["s"].numpy()
+    pk = orc.pack_weights(W, s, 16)
+    Xq, scale = orc.quantize_act(X[:, pk["perm"]], pk["s_inv"], abits)
+    acc = orc.gemm_i32_loops(Xq, pk["Wq"]).astype(np.float64)
+    plain = scale.astype(np.float64)[:, None] * pk["wscale"].astype(np.float64)[None, :] * acc
+    assert np.allclose(orc.linear(Xq, scale, pk["Wq"], pk["wscale"], None), plain, rtol=1e-15)
+    assert np.allclose(orc.linear(Xq, scale, pk["Wq"], pk["wscale"], np.zeros((16, 20))), plain, rtol=1e-15)
+    assert np.allclose(orc.linear(Xq, scale, pk["Wq"], pk["wscale"], np.zeros((0, 20))), plain, rtol=1e-15)
+
+
+@pytest.mark.parametrize("abits,r", [(4, 16), (8, 32)])
+def test_T6_exact_residual_identity(abits, r):
+    """main + compensation == deq(Xq) . [W~_s ; deq(Wq_r)]^T with the unrounded residual (Eq. 5 + Eq. 7)."""
+    spec = workloads.config1().with_(M=7, K=96, N=40, r=r, abits=abits)
+    L = workloads.make_layer(spec)
+    X, W, s = L["X"].float().numpy(), L["W"].float().numpy(), L["s"].numpy()
+    Y, pk = orc.dequant_reference(X, s, W, r, abits)
+    Wt = (W * s[None, :])[:, pk["perm"]].astype(np.float64)          # folded, permuted, unquantised
+    Wmix = pk["wscale"].astype(np.float64)[:, None] * pk["Wq"].astype(np.float64)
+    Wmix[:, :r] = Wt[:, :r]                                           # salient channels exact
+    Xdq = pk["scale"].astype(np.float64)[:, None] * pk["Xq"].astype(np.float64)
+    want = Xdq @ Wmix.T
+    assert np.allclose(Y, want, rtol=1e-12, atol=1e-12 * np.max(np.abs(want)))
+    # a transposed / shifted use of R would not satisfy it
+    Rbad = np.roll(pk["R"], 1, axis=0)
+    Ybad = orc.linear(pk["Xq"], pk["scale"], pk["Wq"], pk["wscale"], Rbad)
+    assert not np.allclose(Ybad, want, rtol=1e-6, atol=1e-9)
+
+
+def test_T7_residual_is_at_most_half_a_step():
+    spec = workloads.config1().with_(K=128, N=64, r=32)
+    L = workloads.make_layer(spec, want=("W", "s"))
+    pk = orc.pack_weights(L["W"].float().numpy(), L["s"].numpy(), 32)
+    assert np.all(np.abs(pk["R"]) <= 0.5 * pk["wscale"].astype(np.float64)[None, :] * (1 + 1e-6))
+    assert np.max(np.abs(pk["R"])) > 0
+
+
+@pytest.mark.parametrize("abits", [4, 8])
+def test_T8_flattening_identity_power_of_two(abits):
+    """(X, W, s) and (X/s, W*s, 1) give bit-identical results when s is exact (Eq. 4)."""
+    spec = workloads.config1().with_(M=6, K=64, N=24, r=16, abits=abits)
+    L = workloads.make_layer(spec)
+    X, W = L["X"].float().numpy(), L["W"].float().numpy()
+    rng = np.random.default_rng(11)
+    s = (2.0 ** rng.integers(-3, 4, size=64)).astype(np.float32)
+    Ya, pa = orc.dequant_reference(X, s, W, 16, abits)
+    Yb, pb = orc.dequant_reference(X / s[None, :], None, W * s[None, :], 16, abits)
+    assert np.array_equal(pa["perm"], pb["perm"])
+    assert np.array_equal(pa["Xq"], pb["Xq"]) and np.array_equal(pa["scale"], pb["scale"])
+    assert np.array_equal(pa["Wq"], pb["Wq"]) and np.array_equal(pa["wscale"], pb["wscale"])
+    assert np.array_equal(Ya, Yb)
+
+
+def test_T9_compensation_reduces_output_error():
+    spec = workloads.config2().with_(M=64, K=512, N=256, r=32, n_outlier=5)
+    L = workloads.make_layer(spec)
+    X, W, s = L["X"].float().numpy(), L["W"].float().numpy(), L["s"].numpy()
+    exact = X.astype(np.float64) @ W.astype(np.float64).T
+    errs = []
+    for r in (0, 8, 32):
+        Y, pk = orc.dequant_reference(X, s, W, r, 4)
+        errs.append(np.linalg.norm(Y - exact))
+        if r:
+            assert set(L["outliers"].tolist()) <= set(pk["perm"][:8].tolist())
+    assert errs[2] < errs[1] < errs[0]
+
+
+def test_gemm_matches_loops_and_int64():
+    rng = np.random.default_rng(3)
+    Xq = rng.integers(-127, 128, size=(5, 40)).astype(np.int8)
+    Wq = rng.integers(-7, 8, size=(9, 40)).astype(np.int8)
+    a = orc.gemm_i32(Xq, Wq)
+    assert a.dtype == np.int32
+    assert np.array_equal(a, orc.gemm_i32_loops(Xq, Wq))
+    assert np.array_equal(a.astype(np.int64), Xq.astype(np.int64) @ Wq.astype(np.int64).T)
+    # extreme magnitudes at a large K stay exact
+    Xq = np.full((2, 16384), -127, np.int8)
+    Wq = np.full((3, 16384), 7, np.int8)
+    assert np.all(orc.gemm_i32(Xq, Wq) == -127 * 7 * 16384)
+
+
+def test_lowrank_uses_the_salient_block_only():
+    rng = np.random.default_rng(9)
+    Xq = rng.integers(-7, 8, size=(4, 64)).astype(np.int8)
+    R = rng.standard_normal((16, 6))
+    want = np.zeros((4, 6))
+    for m in range(4):
+        for n in range(6):
+            want[m, n] = sum(float(Xq[m, 16 + j]) * R[j, n] for j in range(16))
+    assert np.allclose(orc.lowrank(Xq, R, s_begin=16), want, rtol=1e-14, atol=1e-14)
+
+
+def test_T11_effective_weight_bits():
+    # group-128 scales alone: 4 + 16/128 (Table 2, "4.13")
+    assert orc.effective_weight_bits(4096, 4096, 0, group=128) == pytest.approx(4.125)
+    # LLaMA-2-7B decoder layer mix with r = 128, 4-bit R (Table 1, "4.24")
+    layers = [(4096, 4096)] * 4 + [(4096, 11008)] * 2 + [(11008, 4096)]
+    tot = sum(k * n for k, n in layers)
+    eff = sum(orc.effective_weight_bits(k, n, 128, group=128) * k * n for k, n in layers) / tot
+    assert 4.225 <= eff <= 4.245
+    # 8-bit low-rank factors of the same parameter count (Table 1, "4.35" for the two-factor baseline)
+    eff8 = sum(orc.effective_weight_bits(k, n, 128, group=128, r_bits=8) * k * n for k, n in layers) / tot
+    assert 4.33 <= eff8 <= 4.355
