@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the SERQ linear hot path on one MI355X.
+
+A step is one pass of the whole online path over one batch of synthetic
+activations that are already resident in HBM: serq_quantize_act (flatten +
+per-token INT8 quantisation) followed by serq_linear (INT4-weight int8-MFMA
+GEMM with the rank-128 compensation and the dequantising epilogue fused).
+Workload: the up projection of the MLP pair, W4A8, M = 4096 tokens,
+K = 4096 -> N = 11008, r = 128, bf16 in / bf16 out.
+
+Prints ONE JSON line.  `value` is 2*M*N*K / step time in TOPS.  `roofline`
+prices the dominant kernel (serq_linear) against the int8 MFMA peak using its
+own launch durations, measured with HIP events on the launch stream inside the
+timed region.  `decode` reports the M = 1 weight-streaming kernel in GB/s with
+the weight copies rotated so that the working set exceeds the Infinity Cache.
+`cpu_baseline` is the NumPy oracle timed on a bounded sample of the same
+workload on this host's cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads  # noqa: E402
+from paper_2603_08185_amd import binding as serq  # noqa: E402
+
+INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, 5.0 POP/s
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, 8 TB/s
+
+
+def _events(n):
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def bench_prefill(steps: int, warmup: int):
+    spec = workloads.config3("up", 4096)
+    L = workloads.make_layer(spec)
+    dev = "cuda:0"
+    pk = serq.pack_weights(L["W"].to(dev), L["s"].to(dev), spec.r, r_dtype=torch.bfloat16, want_R=False, want_Rp=False)
+    Rp = serq.pack_lowrank(L["R"].to(dev))
+    Xhat = workloads.permute_channels(L["X"], pk.perm.cpu().numpy()).to(dev)
+    M, N, K = spec.M, spec.N, spec.K
+    Xq = torch.empty(M * K, dtype=torch.uint8, device=dev)
+    scale = torch.empty(M, dtype=torch.float32, device=dev)
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+
+    def step():
+        serq.quantize_act(Xhat, pk.s_inv, spec.abits, Xq=Xq, scale=scale)
+        serq.linear(Xq, scale, spec.abits, pk.Wq, pk.wscale, M, N, K, Rp=Rp, r=spec.r, Y=Y)
+
+    for _ in range(warmup):
+        step()
+    ev = _events(2 * steps + 1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev[0].record()
+    for i in range(steps):
+        serq.quantize_act(Xhat, pk.s_inv, spec.abits, Xq=Xq, scale=scale)
+        ev[2 * i + 1].record()
+        serq.linear(Xq, scale, spec.abits, pk.Wq, pk.wscale, M, N, K, Rp=Rp, r=spec.r, Y=Y)
+        ev[2 * i + 2].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    total_ms = ev[0].elapsed_time(ev[-1])
+    q_ms = float(np.mean([ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(steps)]))
+    l_ms = float(np.mean([ev[2 * i + 1].elapsed_time(ev[2 * i + 2]) for i in range(steps)]))
+    ops = 2.0 * M * N * K
+    qbytes = 2.0 * M * K + M * K * spec.abits / 8 + 4 * M
+    return {
+        "spec": spec, "ms_per_step": total_ms / steps, "wall_ms_per_step": wall * 1e3 / steps,
+        "quant_ms": q_ms, "linear_ms": l_ms, "ops": ops,
+        "tops_step": ops / (total_ms / steps * 1e-3) / 1e12,
+        "tops_linear": ops / (l_ms * 1e-3) / 1e12,
+        "quant_gbs": qbytes / (q_ms * 1e-3) / 1e9,
+        "layer": (L, pk),
+    }
+
+
+def decode_bytes(spec) -> float:
+    """Algorithmic HBM bytes of one decode-sized serq_linear call."""
+    M, N, K, r = spec.M, spec.N, spec.K, spec.r
+    out_b = 2 if spec.out_dtype != "fp32" else 4
+    return N * K / 2 + 2.0 * r * N + 4 * N + M * K * spec.abits / 8 + 4 * M + M * N * out_b
+
+
+def bench_decode(L, pk, iters: int = 200):
+    """M = 1 on the same layer; weights + R rotated over > 512 MB of distinct copies."""
+    dev = "cuda:0"
+    spec = workloads.config3("up", 1)
+    M, N, K = 1, spec.N, spec.K
+    X1 = workloads.make_layer(spec, want=("X",))["X"]
+    Xhat = workloads.permute_channels(X1, pk.perm.cpu().numpy()).to(dev)
+    Xq, scale = serq.quantize_act(Xhat, pk.s_inv, spec.abits)
+    Rp0 = serq.pack_lowrank(L["R"].to(dev))
+    per_copy = pk.Wq.numel() + Rp0.numel()
+    ncopy = int(np.ceil(640e6 / per_copy))
+    Wqs = [pk.Wq.clone() for _ in range(ncopy)]
+    Rps = [Rp0.clone() for _ in range(ncopy)]
+    ws = serq.workspace(M, N, K, spec.r, spec.abits, dev)
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+
+    def run(rotate: bool, n: int):
+        e0, e1 = _events(2)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n):
+            j = i % ncopy if rotate else 0
+            serq.linear(Xq, scale, spec.abits, Wqs[j], pk.wscale, M, N, K, Rp=Rps[j], r=spec.r, Y=Y, ws=ws)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    run(True, 2 * ncopy)
+    cold = min(run(True, iters) for _ in range(3))
+    warm = min(run(False, iters) for _ in range(3))
+    b = decode_bytes(spec)
+    return {"workload": spec.name, "bytes": b, "copies": ncopy,
+            "us_hbm": cold * 1e3, "gbs_hbm": b / (cold * 1e-3) / 1e9,
+            "us_cache_warm": warm * 1e3, "gbs_cache_warm": b / (warm * 1e-3) / 1e9,
+            "frac_hbm_peak": b / (cold * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+
+def cpu_baseline(L, n_tokens: int = 192):
+    """The oracle, as it stands, on a sample of the workload's tokens (all N, all K)."""
+    from threadpoolctl import threadpool_info
+    from oracle import serq_oracle as orc
+    spec = workloads.config3("up", 4096)
+    W = L["W"].float().numpy()
+    pk = orc.pack_weights(W, L["s"].numpy(), spec.r)           # offline: not timed
+    R = L["R"].double().numpy()
+    X = L["X"][:n_tokens].float().numpy()[:, pk["perm"]]
+    t0 = time.perf_counter()
+    Xq, scale = orc.quantize_act(X, pk["s_inv"], spec.abits)
+    Y = orc.linear(Xq, scale, pk["Wq"], pk["wscale"], R)
+    dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    ops = 2.0 * n_tokens * spec.N * spec.K
+    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n_tokens} of 4096 tokens, full N=11008, K=4096, r=128 (quantize_act + gemm + epilogue), "
+                      f"{dt:.2f} s", "host_cpus": len(os.sched_getaffinity(0))}, Y
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-decode", action="store_true", help="skip the M=1 decode leg")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    serq.lib()
+
+    pre = bench_prefill(a.steps, a.warmup)
+    spec = pre["spec"]
+    L, pk = pre["layer"]
+    out = {
+        "metric": "fused SERQ linear TOPS (M=4096, 4096x11008) + decode GB/s (M=1), 1 MI355X",
+        "value": round(pre["tops_step"], 2), "unit": "TOPS",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(pre["ms_per_step"], 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "configs[2]: MLP up projection W4A8, M=4096, K=4096->N=11008, r=128, bf16 in/out; "
+                               "step = serq_quantize_act + serq_linear",
+                   "M": spec.M, "K": spec.K, "N": spec.N, "r": spec.r, "abits": spec.abits},
+        "roofline": {"bound": "mfma", "kernel": "serq_mfma_kernel<8> (serq_linear)",
+                     "achieved": round(pre["tops_linear"], 2), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": round(pre["tops_linear"] / INT8_PEAK_TOPS, 4), "traffic": None,
+                     "kernel_ms": round(pre["linear_ms"], 5)},
+        "quantize_act": {"ms": round(pre["quant_ms"], 5), "gbs": round(pre["quant_gbs"], 1),
+                         "frac_hbm_peak": round(pre["quant_gbs"] / HBM_PEAK_GBS, 4)},
+    }
+    if not a.no_decode:
+        d = bench_decode(L, pk)
+        out["decode"] = {k: (round(v, 3) if isinstance(v, float) else v) for k, v in d.items()}
+    if not a.no_cpu:
+        cb, _ = cpu_baseline(L)
+        cb["value"] = round(cb["value"], 5)
+        out["cpu_baseline"] = cb
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,163 @@
+/*
+ * serq.h -- C ABI of the MI355X (gfx950) SERQ linear-layer library.
+ *
+ * The library implements the online hot path of SERQ (saliency-aware low-rank
+ * error reconstruction): per-token activation quantisation, the INT4-weight
+ * integer GEMM, and the single rank-r compensation fused into the
+ * dequantising epilogue, plus the offline weight preparation.
+ *
+ * Conventions for every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller, 16-byte
+ *     aligned.  The library allocates nothing and keeps no state between
+ *     calls; all work is enqueued on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and returns without waiting.
+ *   - Matrices are row-major.  X is [M tokens, K input channels]; W is
+ *     [N output channels, K input channels]; R is [r, N]; Y is [M, N].
+ *     (The paper writes Y = X.W with W [d_in, d_out]: one of its "weight
+ *     rows" -- an input channel -- is a column of our W.)
+ *   - The activations handed to the online calls are ALREADY in the permuted
+ *     channel order the packed weights use (the offline permutation of
+ *     Sec. 3.2 guarantees this; there is no online gather).
+ *   - Return value: SERQ_OK or a negative SERQ_E* code; nothing throws or
+ *     aborts.  Non-finite inputs give undefined outputs, not an error.
+ *   - Shape limits: K a multiple of 64, 64 <= K <= 131072; N a multiple of
+ *     32; r a multiple of 16 with s_begin + r <= K, s_begin a multiple of 16.
+ *   - Packed tensors (Xq, Wq, Rp) have library-private layouts; use the
+ *     serq_unpack_* calls to read them back in canonical form.
+ */
+#ifndef SERQ_H_
+#define SERQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* error codes */
+#define SERQ_OK            0
+#define SERQ_ENULL        -1   /* a required pointer is NULL                    */
+#define SERQ_EDTYPE       -2   /* unsupported dtype / activation bit-width      */
+#define SERQ_ESHAPE       -3   /* a size violates the limits above              */
+#define SERQ_EALIGN       -4   /* pointer or leading dimension misaligned       */
+#define SERQ_EWORKSPACE   -5   /* workspace missing or too small                */
+#define SERQ_EHIP         -6   /* the HIP runtime reported a launch error       */
+#define SERQ_EUNSUPPORTED -7   /* valid request this build does not implement   */
+
+/* element types of caller-visible tensors */
+#define SERQ_F32  0
+#define SERQ_F16  1
+#define SERQ_BF16 2
+
+/* kernel selection for serq_linear / serq_gemm_i32 (low byte of `flags`) */
+#define SERQ_PATH_AUTO   0     /* by M: skinny for M <= 32, tiled MFMA above    */
+#define SERQ_PATH_SKINNY 1     /* weight-streaming split-K kernel (M <= 32)     */
+#define SERQ_PATH_MFMA   2     /* LDS-tiled int8-MFMA kernel                    */
+/* bits 8..15 of `flags`: split-K factor override for the skinny path (0 = auto) */
+#define SERQ_FLAG_SPLITK(n) (((n) & 0xff) << 8)
+/* bits 16..19 of `flags`: token-tile group height of the MFMA path's block order (0 = auto) */
+#define SERQ_FLAG_GROUPM(n) (((n) & 0xf) << 16)
+
+int         serq_version(void);
+const char* serq_strerror(int code);
+
+/* Sizes of the caller-allocated buffers, in bytes (0 on invalid arguments). */
+size_t serq_packed_act_bytes(int64_t M, int64_t K, int abits);     /* Xq                    */
+size_t serq_packed_weight_bytes(int64_t N, int64_t K);             /* Wq                    */
+size_t serq_packed_lowrank_bytes(int64_t N, int r);                /* Rp (16-bit elements)  */
+size_t serq_workspace_bytes(int64_t M, int64_t N, int64_t K, int r, int abits);
+
+/* Zero a workspace before its first use.  serq_linear / serq_gemm_i32 leave it
+ * zeroed again when they finish, so one call after allocation is enough.  Two
+ * calls that share a workspace must not overlap in time. */
+int serq_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Offline preparation of one layer (Sec. 3.2: Eq. 4 static flattening folded
+ * into the weights, saliency order P and the permuted weights of Eq. 5/6,
+ * per-output-channel symmetric INT4 quantisation per Eq. 1, and the
+ * compensation matrix R = W~_s - Q(W~_s) of Eq. 5).
+ *
+ *   W        [N,K] fp16/bf16/fp32 (w_dtype), ORIGINAL channel order.
+ *   s        [K] fp32 flattening vector (weights are multiplied by s, the
+ *            activations by 1/s); NULL = all ones.
+ *   perm_in  [K] int32, perm_in[kp] = original channel placed at permuted
+ *            position kp; NULL = order by saliency: channel scale
+ *            max_n |W[n,k]*s[k]|, descending, ties to the lower index.
+ *            A caller-supplied perm_in must be a permutation (not checked).
+ *   Wq_out   serq_packed_weight_bytes(N,K) bytes.
+ *   wscale_out [N] fp32: max_k |W~[n,k]| / 7 (1.0 for an all-zero row).
+ *   perm_out [K] int32 (required; equals perm_in when that is given).
+ *   s_inv_out [K] fp32 (required): 1/s in permuted order -- what
+ *            serq_quantize_act multiplies by.
+ *   R_out    [r,N] in r_dtype, the residual of the r leading (salient)
+ *            channels, rounded to nearest even; may be NULL.
+ *   Rp_out   the same residual in the packed layout serq_linear reads
+ *            (serq_packed_lowrank_bytes(N,r)); may be NULL.  r_dtype must be
+ *            SERQ_F16 or SERQ_BF16 when Rp_out is given.
+ *   r may be 0 (then R_out / Rp_out are ignored).
+ */
+int serq_pack_weights(const void* W, int w_dtype, const float* s, const int32_t* perm_in,
+                      int64_t N, int64_t K, int r,
+                      void* Wq_out, float* wscale_out, int32_t* perm_out, float* s_inv_out,
+                      void* R_out, int r_dtype, void* Rp_out, void* stream);
+
+/* Re-layout a caller-supplied compensation matrix R [r,N] (fp16/bf16) into the
+ * packed form serq_linear reads (the single matrix of Eq. 5 / Eq. 7). */
+int serq_pack_lowrank(const void* R, int r_dtype, int64_t N, int r, void* Rp_out, void* stream);
+
+/* Canonical views of the packed tensors (parity checks). */
+int serq_unpack_lowrank(const void* Rp, int64_t N, int r, void* R_out, void* stream);   /* 16-bit [r,N] */
+int serq_unpack_weights(const void* Wq, int64_t N, int64_t K, int8_t* Wq_i8_out, void* stream); /* [N,K] */
+int serq_unpack_act(const void* Xq, int abits, int64_t M, int64_t K, int8_t* Xq_i8_out, void* stream); /* [M,K] */
+
+/*
+ * Online step 1: static activation flattening (Eq. 4) + per-token symmetric
+ * max-scaled quantisation (Eq. 1), round-half-to-even, codes in
+ * [-(2^(abits-1)-1), +(2^(abits-1)-1)].
+ *
+ *   X      [M,K] fp16/bf16/fp32 (x_dtype), row stride ldx elements (multiple of 8).
+ *   s_inv  [K] fp32 from serq_pack_weights, or NULL when X is already flattened.
+ *   abits  4 or 8.
+ *   Xq_out serq_packed_act_bytes(M,K,abits) bytes; scale_out [M] fp32:
+ *          scale[m] = max_k |X[m,k]*s_inv[k]| / qmax in fp32 (1.0 for a zero token).
+ * M may be 0 (nothing is done).
+ */
+int serq_quantize_act(const void* X, int x_dtype, const float* s_inv,
+                      int64_t M, int64_t K, int64_t ldx, int abits,
+                      void* Xq_out, float* scale_out, void* stream);
+
+/*
+ * Online step 2: the SERQ linear layer (Eq. 2 + Eq. 7, first line)
+ *
+ *   Y[m,n] = scale[m] * ( wscale[n] * sum_k Xq[m,k]*Wq[n,k]
+ *                         + sum_{j<r} Xq[m, s_begin+j] * R[j,n] )
+ *
+ * with the integer sum exact in INT32 (int8 MFMA) and the rest in fp32; Y is
+ * written once.  Rp is the packed compensation matrix (fp16 or bf16 per
+ * r_dtype); r = 0 or Rp = NULL gives the plain W4A4 / W4A8 GEMM.
+ *   Y [M,N] in y_dtype (fp32/fp16/bf16), row stride ldy elements (multiple of 8).
+ *   workspace: serq_workspace_bytes(...) bytes prepared by serq_workspace_init
+ *   (needed only when the skinny path splits K; pass NULL/0 to forbid that).
+ *   flags: SERQ_PATH_* | SERQ_FLAG_*.
+ */
+int serq_linear(const void* Xq, const float* scale, int abits,
+                const void* Wq, const float* wscale,
+                int s_begin, int r, const void* Rp, int r_dtype,
+                int64_t M, int64_t N, int64_t K,
+                void* Y, int y_dtype, int64_t ldy,
+                void* workspace, size_t workspace_bytes, int flags, void* stream);
+
+/* Parity aid: the same main loops, storing the raw INT32 accumulators
+ * acc[m,n] = sum_k Xq[m,k]*Wq[n,k] (first term of Eq. 7) to acc_out [M,N],
+ * row stride ldacc elements (multiple of 4). */
+int serq_gemm_i32(const void* Xq, int abits, const void* Wq,
+                  int64_t M, int64_t N, int64_t K,
+                  int32_t* acc_out, int64_t ldacc,
+                  void* workspace, size_t workspace_bytes, int flags, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SERQ_H_ */

@@ -1,0 +1,213 @@
+"""ctypes binding of libserq.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/serq.h).
+PyTorch supplies device memory and the current stream; no arithmetic of the
+method happens in Python.  If the shared library is missing the import of
+this module's `lib()` raises -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libserq.so")
+
+F32, F16, BF16 = 0, 1, 2
+PATH_AUTO, PATH_SKINNY, PATH_MFMA = 0, 1, 2
+
+_DT = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
+
+# name -> (restype, argtypes): mirrors include/serq.h declaration by declaration
+_vp, _i, _i64, _sz = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
+SIGNATURES = {
+    "serq_version": (_i, []),
+    "serq_strerror": (C.c_char_p, [_i]),
+    "serq_packed_act_bytes": (_sz, [_i64, _i64, _i]),
+    "serq_packed_weight_bytes": (_sz, [_i64, _i64]),
+    "serq_packed_lowrank_bytes": (_sz, [_i64, _i]),
+    "serq_workspace_bytes": (_sz, [_i64, _i64, _i64, _i, _i]),
+    "serq_workspace_init": (_i, [_vp, _sz, _vp]),
+    "serq_pack_weights": (_i, [_vp, _i, _vp, _vp, _i64, _i64, _i, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp]),
+    "serq_pack_lowrank": (_i, [_vp, _i, _i64, _i, _vp, _vp]),
+    "serq_unpack_lowrank": (_i, [_vp, _i64, _i, _vp, _vp]),
+    "serq_unpack_weights": (_i, [_vp, _i64, _i64, _vp, _vp]),
+    "serq_unpack_act": (_i, [_vp, _i, _i64, _i64, _vp, _vp]),
+    "serq_quantize_act": (_i, [_vp, _i, _vp, _i64, _i64, _i64, _i, _vp, _vp, _vp]),
+    "serq_linear": (_i, [_vp, _vp, _i, _vp, _vp, _i, _i, _vp, _i, _i64, _i64, _i64, _vp, _i, _i64,
+                         _vp, _sz, _i, _vp]),
+    "serq_gemm_i32": (_i, [_vp, _i, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _sz, _i, _vp]),
+}
+
+_lib = None
+
+
+class SerqError(RuntimeError):
+    def __init__(self, fn: str, code: int):
+        msg = lib().serq_strerror(code).decode()
+        super().__init__(f"{fn} failed: {msg} ({code})")
+        self.code = code
+
+
+def lib() -> C.CDLL:
+    """Load libserq.so (built by paper_2603_08185_amd/build.py).  Raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} not found: build it with `python -m paper_2603_08185_amd.build` "
+                "(the SERQ kernels have no fallback implementation)")
+        L = C.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(fn: str, rc: int):
+    if rc != 0:
+        raise SerqError(fn, rc)
+
+
+def _dev(t: torch.Tensor, name: str):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+
+
+def flags(path: int = PATH_AUTO, splitk: int = 0, groupm: int = 0) -> int:
+    return (path & 0xff) | ((splitk & 0xff) << 8) | ((groupm & 0xf) << 16)
+
+
+def workspace(M: int, N: int, K: int, r: int, abits: int, device) -> torch.Tensor:
+    n = lib().serq_workspace_bytes(M, N, K, r, abits)
+    ws = torch.empty(max(n, 16), dtype=torch.uint8, device=device)
+    _check("serq_workspace_init", lib().serq_workspace_init(_ptr(ws), ws.numel(), _stream()))
+    return ws
+
+
+@dataclass
+class PackedLayer:
+    """Device-resident artefacts of serq_pack_weights for one layer."""
+    N: int
+    K: int
+    r: int
+    Wq: torch.Tensor        # uint8 blob
+    wscale: torch.Tensor    # fp32 [N]
+    perm: torch.Tensor      # int32 [K]
+    s_inv: torch.Tensor     # fp32 [K]
+    R: Optional[torch.Tensor]    # [r,N] canonical residual (r_dtype) or None
+    Rp: Optional[torch.Tensor]   # packed residual or None
+
+
+def pack_weights(W: torch.Tensor, s: Optional[torch.Tensor], r: int, perm_in: Optional[torch.Tensor] = None,
+                 r_dtype: torch.dtype = torch.bfloat16, want_R: bool = True, want_Rp: bool = True) -> PackedLayer:
+    _dev(W, "W")
+    N, K = W.shape
+    L = lib()
+    nbytes = L.serq_packed_weight_bytes(N, K)
+    if nbytes == 0:
+        raise SerqError("serq_packed_weight_bytes", -3)
+    dev = W.device
+    Wq = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    wscale = torch.empty(N, dtype=torch.float32, device=dev)
+    perm = torch.empty(K, dtype=torch.int32, device=dev)
+    s_inv = torch.empty(K, dtype=torch.float32, device=dev)
+    R = torch.empty((r, N), dtype=r_dtype, device=dev) if (r > 0 and want_R) else None
+    Rp = None
+    if r > 0 and want_Rp and r_dtype in (torch.float16, torch.bfloat16):
+        Rp = torch.empty(L.serq_packed_lowrank_bytes(N, r), dtype=torch.uint8, device=dev)
+    if s is not None:
+        _dev(s, "s")
+    if perm_in is not None:
+        _dev(perm_in, "perm_in")
+    rc = L.serq_pack_weights(_ptr(W), _DT[W.dtype], _ptr(s), _ptr(perm_in), N, K, r, _ptr(Wq), _ptr(wscale),
+                             _ptr(perm), _ptr(s_inv), _ptr(R), _DT[r_dtype], _ptr(Rp), _stream())
+    _check("serq_pack_weights", rc)
+    return PackedLayer(N, K, r, Wq, wscale, perm, s_inv, R, Rp)
+
+
+def pack_lowrank(R: torch.Tensor) -> torch.Tensor:
+    _dev(R, "R")
+    r, N = R.shape
+    L = lib()
+    Rp = torch.empty(max(L.serq_packed_lowrank_bytes(N, r), 16), dtype=torch.uint8, device=R.device)
+    _check("serq_pack_lowrank", L.serq_pack_lowrank(_ptr(R), _DT[R.dtype], N, r, _ptr(Rp), _stream()))
+    return Rp
+
+
+def unpack_lowrank(Rp: torch.Tensor, N: int, r: int, dtype: torch.dtype) -> torch.Tensor:
+    out = torch.empty((r, N), dtype=dtype, device=Rp.device)
+    _check("serq_unpack_lowrank", lib().serq_unpack_lowrank(_ptr(Rp), N, r, _ptr(out), _stream()))
+    return out
+
+
+def unpack_weights(Wq: torch.Tensor, N: int, K: int) -> torch.Tensor:
+    out = torch.empty((N, K), dtype=torch.int8, device=Wq.device)
+    _check("serq_unpack_weights", lib().serq_unpack_weights(_ptr(Wq), N, K, _ptr(out), _stream()))
+    return out
+
+
+def unpack_act(Xq: torch.Tensor, abits: int, M: int, K: int) -> torch.Tensor:
+    out = torch.empty((M, K), dtype=torch.int8, device=Xq.device)
+    _check("serq_unpack_act", lib().serq_unpack_act(_ptr(Xq), abits, M, K, _ptr(out), _stream()))
+    return out
+
+
+def quantize_act(X: torch.Tensor, s_inv: Optional[torch.Tensor], abits: int,
+                 Xq: Optional[torch.Tensor] = None, scale: Optional[torch.Tensor] = None):
+    """serq_quantize_act: returns (Xq packed uint8 blob, scale fp32 [M])."""
+    if not X.is_cuda:
+        raise ValueError("X must live in device memory")
+    if X.dim() != 2 or X.stride(1) != 1:
+        raise ValueError("X must be [M,K] with unit inner stride")
+    M, K = X.shape
+    L = lib()
+    if Xq is None:
+        Xq = torch.empty(max(L.serq_packed_act_bytes(M, K, abits), 16), dtype=torch.uint8, device=X.device)
+    if scale is None:
+        scale = torch.empty(max(M, 1), dtype=torch.float32, device=X.device)[:M]
+    ldx = X.stride(0) if M > 0 else K
+    rc = L.serq_quantize_act(_ptr(X), _DT[X.dtype], _ptr(s_inv), M, K, ldx, abits, _ptr(Xq), _ptr(scale), _stream())
+    _check("serq_quantize_act", rc)
+    return Xq, scale
+
+
+def linear(Xq: torch.Tensor, scale: torch.Tensor, abits: int, Wq: torch.Tensor, wscale: torch.Tensor,
+           M: int, N: int, K: int, Rp: Optional[torch.Tensor] = None, r: int = 0,
+           r_dtype: torch.dtype = torch.bfloat16, s_begin: int = 0,
+           out_dtype: torch.dtype = torch.bfloat16, Y: Optional[torch.Tensor] = None,
+           ws: Optional[torch.Tensor] = None, flags_: int = 0) -> torch.Tensor:
+    """serq_linear: Y = scale * (wscale * (Xq . Wq^T) + Xq[:, S] . R)."""
+    if Y is None:
+        Y = torch.empty((M, N), dtype=out_dtype, device=Xq.device)
+    rc = lib().serq_linear(_ptr(Xq), _ptr(scale), abits, _ptr(Wq), _ptr(wscale), s_begin, r, _ptr(Rp),
+                           _DT[r_dtype], M, N, K, _ptr(Y), _DT[Y.dtype], Y.stride(0),
+                           _ptr(ws), 0 if ws is None else ws.numel(), flags_, _stream())
+    _check("serq_linear", rc)
+    return Y
+
+
+def gemm_i32(Xq: torch.Tensor, abits: int, Wq: torch.Tensor, M: int, N: int, K: int,
+             ws: Optional[torch.Tensor] = None, flags_: int = 0) -> torch.Tensor:
+    """serq_gemm_i32: the raw INT32 accumulators [M,N]."""
+    acc = torch.empty((M, N), dtype=torch.int32, device=Xq.device)
+    rc = lib().serq_gemm_i32(_ptr(Xq), abits, _ptr(Wq), M, N, K, _ptr(acc), N,
+                             _ptr(ws), 0 if ws is None else ws.numel(), flags_, _stream())
+    _check("serq_gemm_i32", rc)
+    return acc

@@ -1,0 +1,214 @@
+// C ABI of the library: argument checking and dispatch only (see include/serq.h).
+#include "serq_device.h"
+
+using namespace serq;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool dtype_ok(int dt) { return dt == SERQ_F32 || dt == SERQ_F16 || dt == SERQ_BF16; }
+inline bool dtype16(int dt) { return dt == SERQ_F16 || dt == SERQ_BF16; }
+
+int check_nk(int64_t N, int64_t K) {
+  if (K < 64 || K > 131072 || (K % 64) != 0) return SERQ_ESHAPE;
+  if (N < 32 || (N % 32) != 0 || N > (1 << 24)) return SERQ_ESHAPE;
+  return SERQ_OK;
+}
+
+// plain fill kernel: safe to record into a HIP graph, unlike a memset node
+__global__ __launch_bounds__(256) void zero_fill_kernel(uint32_t* p, size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0u;
+}
+
+int check_lowrank(int64_t K, int s_begin, int r) {
+  if (r < 0 || (r % 16) != 0 || s_begin < 0 || (s_begin % 16) != 0) return SERQ_ESHAPE;
+  if ((int64_t)s_begin + r > K) return SERQ_ESHAPE;
+  return SERQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int serq_version(void) { return 100; }
+
+const char* serq_strerror(int code) {
+  switch (code) {
+    case SERQ_OK: return "ok";
+    case SERQ_ENULL: return "required pointer is NULL";
+    case SERQ_EDTYPE: return "unsupported dtype or activation bit-width";
+    case SERQ_ESHAPE: return "size outside the supported limits";
+    case SERQ_EALIGN: return "pointer or leading dimension misaligned";
+    case SERQ_EWORKSPACE: return "workspace missing or too small";
+    case SERQ_EHIP: return "HIP runtime error";
+    case SERQ_EUNSUPPORTED: return "request not implemented";
+    default: return "unknown error code";
+  }
+}
+
+size_t serq_packed_act_bytes(int64_t M, int64_t K, int abits) {
+  if (M < 0 || K <= 0 || (K % 64) != 0 || (abits != 4 && abits != 8)) return 0;
+  return (size_t)M * (size_t)K * abits / 8;
+}
+
+size_t serq_packed_weight_bytes(int64_t N, int64_t K) {
+  if (check_nk(N, K) != SERQ_OK) return 0;
+  return (size_t)N * (size_t)K / 2;
+}
+
+size_t serq_packed_lowrank_bytes(int64_t N, int r) {
+  if (N <= 0 || (N % 32) != 0 || r < 0 || (r % 16) != 0) return 0;
+  return (size_t)N * (size_t)r * 2;
+}
+
+size_t serq_workspace_bytes(int64_t M, int64_t N, int64_t K, int r, int abits) {
+  (void)r; (void)abits;
+  if (check_nk(N, K) != SERQ_OK || M < 0) return 0;
+  // the skinny path's split-K partial sums and arrival counters; sized for the
+  // largest factor the flags can request
+  int s = skinny_splitk_auto((int)(M > 32 ? 32 : M), (int)N, (int)K);
+  if (s < 8) s = 8;
+  return skinny_workspace_bytes((int)N, s);
+}
+
+int serq_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+  if (workspace_bytes == 0) return SERQ_OK;
+  if (!workspace) return SERQ_ENULL;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 3u) || (workspace_bytes & 3u)) return SERQ_EALIGN;
+  const size_t n = workspace_bytes / 4;
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                     (uint32_t*)workspace, n);
+  return hipGetLastError() == hipSuccess ? SERQ_OK : SERQ_EHIP;
+}
+
+int serq_pack_weights(const void* W, int w_dtype, const float* s, const int32_t* perm_in,
+                      int64_t N, int64_t K, int r,
+                      void* Wq_out, float* wscale_out, int32_t* perm_out, float* s_inv_out,
+                      void* R_out, int r_dtype, void* Rp_out, void* stream) {
+  if (!W || !Wq_out || !wscale_out || !perm_out || !s_inv_out) return SERQ_ENULL;
+  if (!dtype_ok(w_dtype)) return SERQ_EDTYPE;
+  int rc = check_nk(N, K);
+  if (rc != SERQ_OK) return rc;
+  rc = check_lowrank(K, 0, r);
+  if (rc != SERQ_OK) return rc;
+  if (r > 0 && (R_out || Rp_out)) {
+    if (!dtype_ok(r_dtype)) return SERQ_EDTYPE;
+    if (Rp_out && !dtype16(r_dtype)) return SERQ_EDTYPE;
+  }
+  if (!aligned16(W) || !aligned16(Wq_out) || !aligned16(wscale_out) || !aligned16(perm_out) ||
+      !aligned16(s_inv_out) || !aligned16(R_out) || !aligned16(Rp_out) || !aligned16(s) || !aligned16(perm_in))
+    return SERQ_EALIGN;
+  return pack_weights_impl(W, w_dtype, s, perm_in, (int)N, (int)K, r, Wq_out, wscale_out, perm_out, s_inv_out,
+                           R_out, r_dtype, Rp_out, (hipStream_t)stream);
+}
+
+int serq_pack_lowrank(const void* R, int r_dtype, int64_t N, int r, void* Rp_out, void* stream) {
+  if (!R || !Rp_out) return SERQ_ENULL;
+  if (!dtype16(r_dtype)) return SERQ_EDTYPE;
+  if (N < 32 || (N % 32) != 0 || N > (1 << 24) || r < 0 || (r % 16) != 0) return SERQ_ESHAPE;
+  if (!aligned16(R) || !aligned16(Rp_out)) return SERQ_EALIGN;
+  return pack_lowrank_impl(const_cast<void*>(R), (int)N, r, Rp_out, false, (hipStream_t)stream);
+}
+
+int serq_unpack_lowrank(const void* Rp, int64_t N, int r, void* R_out, void* stream) {
+  if (!Rp || !R_out) return SERQ_ENULL;
+  if (N < 32 || (N % 32) != 0 || N > (1 << 24) || r < 0 || (r % 16) != 0) return SERQ_ESHAPE;
+  if (!aligned16(Rp) || !aligned16(R_out)) return SERQ_EALIGN;
+  return pack_lowrank_impl(R_out, (int)N, r, const_cast<void*>(Rp), true, (hipStream_t)stream);
+}
+
+int serq_unpack_weights(const void* Wq, int64_t N, int64_t K, int8_t* out, void* stream) {
+  if (!Wq || !out) return SERQ_ENULL;
+  const int rc = check_nk(N, K);
+  if (rc != SERQ_OK) return rc;
+  if (!aligned16(Wq) || !aligned16(out)) return SERQ_EALIGN;
+  return unpack_weights_impl(Wq, (int)N, (int)K, out, (hipStream_t)stream);
+}
+
+int serq_unpack_act(const void* Xq, int abits, int64_t M, int64_t K, int8_t* out, void* stream) {
+  if (abits != 4 && abits != 8) return SERQ_EDTYPE;
+  if (M < 0 || K < 64 || K > 131072 || (K % 64) != 0) return SERQ_ESHAPE;
+  if (M == 0) return SERQ_OK;
+  if (!Xq || !out) return SERQ_ENULL;
+  if (!aligned16(Xq) || !aligned16(out)) return SERQ_EALIGN;
+  return unpack_act_impl(Xq, abits, M, (int)K, out, (hipStream_t)stream);
+}
+
+int serq_quantize_act(const void* X, int x_dtype, const float* s_inv,
+                      int64_t M, int64_t K, int64_t ldx, int abits,
+                      void* Xq_out, float* scale_out, void* stream) {
+  if (abits != 4 && abits != 8) return SERQ_EDTYPE;
+  if (!dtype_ok(x_dtype)) return SERQ_EDTYPE;
+  if (M < 0 || K < 64 || K > 131072 || (K % 64) != 0) return SERQ_ESHAPE;
+  if (ldx < K) return SERQ_ESHAPE;
+  if ((ldx % 8) != 0) return SERQ_EALIGN;
+  if (M == 0) return SERQ_OK;
+  if (!X || !Xq_out || !scale_out) return SERQ_ENULL;
+  if (!aligned16(X) || !aligned16(Xq_out) || !aligned16(s_inv) || (reinterpret_cast<uintptr_t>(scale_out) & 3u))
+    return SERQ_EALIGN;
+  return launch_quantize_act(X, x_dtype, s_inv, M, (int)K, ldx, abits, Xq_out, scale_out, (hipStream_t)stream);
+}
+
+static int linear_common(LinearArgs& a, int64_t M, int64_t N, int64_t K, int flags, void* stream) {
+  if (a.abits != 4 && a.abits != 8) return SERQ_EDTYPE;
+  int rc = check_nk(N, K);
+  if (rc != SERQ_OK) return rc;
+  if (M < 0 || M > (1 << 30)) return SERQ_ESHAPE;
+  if (M == 0) return SERQ_OK;
+  if (!a.Xq || !a.Wq) return SERQ_ENULL;
+  if (!aligned16(a.Xq) || !aligned16(a.Wq) || !aligned16(a.Rp) || !aligned16(a.wscale) || !aligned16(a.workspace))
+    return SERQ_EALIGN;
+  a.M = (int)M; a.N = (int)N; a.K = (int)K;
+  a.splitk = (flags >> 8) & 0xff;
+  a.groupm = (flags >> 16) & 0xf;
+  const int path = flags & 0xff;
+  if (path != SERQ_PATH_AUTO && path != SERQ_PATH_SKINNY && path != SERQ_PATH_MFMA) return SERQ_EUNSUPPORTED;
+  if (path == SERQ_PATH_SKINNY && M > 32) return SERQ_ESHAPE;
+  const bool skinny = path == SERQ_PATH_SKINNY || (path == SERQ_PATH_AUTO && M <= 32);
+  return skinny ? launch_skinny(a, (hipStream_t)stream) : launch_mfma(a, (hipStream_t)stream);
+}
+
+int serq_linear(const void* Xq, const float* scale, int abits,
+                const void* Wq, const float* wscale,
+                int s_begin, int r, const void* Rp, int r_dtype,
+                int64_t M, int64_t N, int64_t K,
+                void* Y, int y_dtype, int64_t ldy,
+                void* workspace, size_t workspace_bytes, int flags, void* stream) {
+  if (!dtype_ok(y_dtype)) return SERQ_EDTYPE;
+  if (M > 0 && (!Y || !scale || !wscale)) return SERQ_ENULL;
+  int rc = check_lowrank(K, s_begin, r);
+  if (rc != SERQ_OK) return rc;
+  if (r > 0 && Rp && !dtype16(r_dtype)) return SERQ_EDTYPE;
+  if (ldy < N) return SERQ_ESHAPE;
+  if ((ldy % 8) != 0 || !aligned16(Y) || (reinterpret_cast<uintptr_t>(scale) & 3u)) return SERQ_EALIGN;
+  LinearArgs a{};
+  a.Xq = (const uint8_t*)Xq; a.scale = scale; a.abits = abits;
+  a.Wq = (const u4*)Wq; a.wscale = wscale;
+  a.s_begin = s_begin; a.r = (Rp ? r : 0); a.Rp = (r > 0 ? (const u4*)Rp : nullptr); a.r_dtype = r_dtype;
+  a.Y = Y; a.y_dtype = y_dtype; a.ldy = ldy;
+  a.acc_out = nullptr; a.ldacc = 0;
+  a.workspace = workspace; a.workspace_bytes = workspace_bytes;
+  return linear_common(a, M, N, K, flags, stream);
+}
+
+int serq_gemm_i32(const void* Xq, int abits, const void* Wq,
+                  int64_t M, int64_t N, int64_t K,
+                  int32_t* acc_out, int64_t ldacc,
+                  void* workspace, size_t workspace_bytes, int flags, void* stream) {
+  if (M > 0 && !acc_out) return SERQ_ENULL;
+  if (ldacc < N) return SERQ_ESHAPE;
+  if ((ldacc % 4) != 0 || !aligned16(acc_out)) return SERQ_EALIGN;
+  LinearArgs a{};
+  a.Xq = (const uint8_t*)Xq; a.scale = nullptr; a.abits = abits;
+  a.Wq = (const u4*)Wq; a.wscale = nullptr;
+  a.s_begin = 0; a.r = 0; a.Rp = nullptr; a.r_dtype = SERQ_BF16;
+  a.Y = nullptr; a.y_dtype = SERQ_F32; a.ldy = 0;
+  a.acc_out = acc_out; a.ldacc = ldacc;
+  a.workspace = workspace; a.workspace_bytes = workspace_bytes;
+  return linear_common(a, M, N, K, flags, stream);
+}
+
+}  // extern "C"

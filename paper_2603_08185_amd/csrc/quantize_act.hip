@@ -1,0 +1,188 @@
+// Per-token activation flattening + symmetric quantisation + packing.
+//
+// Sec. 3.2 Eq. 4 (X~ = X diag(1/s)) followed by Sec. 2.1 Eq. 1 per token:
+//   scale[m] = max_k |x~| / qmax,  code = clip(rne(x~ / scale), -qmax, qmax).
+// One 256-thread workgroup per token; the row is read from HBM once, in
+// 16-byte pieces, and kept in registers between the absmax pass and the
+// quantise pass.  All arithmetic that decides a code is IEEE fp32 (one
+// multiply, one division, one round-to-nearest-even), so the codes do not
+// depend on how the reduction is scheduled.
+#include "serq_device.h"
+
+namespace serq {
+namespace {
+
+constexpr int kThreads = 256;
+
+template <int XDT>
+__device__ __forceinline__ void load8(const void* row, int chunk, float v[8]) {
+  if constexpr (XDT == SERQ_F32) {
+    const float4* p = (const float4*)row + 2 * (size_t)chunk;
+    float4 a = p[0], b = p[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  } else {
+    uint4 u = ((const uint4*)row)[chunk];
+    uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if constexpr (XDT == SERQ_BF16) {
+        v[2 * i] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+      } else {
+        v[2 * i] = f16_to_f32((uint16_t)(w[i] & 0xffffu));
+        v[2 * i + 1] = f16_to_f32((uint16_t)(w[i] >> 16));
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ void flatten8(const float* s_inv, int chunk, float v[8]) {
+  if (s_inv) {
+    const float4* p = (const float4*)s_inv + 2 * (size_t)chunk;
+    float4 a = p[0], b = p[1];
+    v[0] *= a.x; v[1] *= a.y; v[2] *= a.z; v[3] *= a.w;
+    v[4] *= b.x; v[5] *= b.y; v[6] *= b.z; v[7] *= b.w;
+  }
+}
+
+__device__ __forceinline__ float absmax8(const float v[8], float m) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) m = fmaxf(m, fabsf(v[i]));
+  return m;
+}
+
+template <int ABITS>
+__device__ __forceinline__ void quant_store8(const float v[8], float sc, void* xq_row, int chunk) {
+  constexpr float q = (float)((1 << (ABITS - 1)) - 1);
+  int c[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    float t = rintf(v[i] / sc);            // IEEE division, then round-half-to-even
+    t = fminf(fmaxf(t, -q), q);
+    c[i] = (int)t;
+  }
+  if constexpr (ABITS == 8) {
+    uint32_t d0 = (c[0] & 0xff) | ((c[1] & 0xff) << 8) | ((c[2] & 0xff) << 16) | ((uint32_t)(c[3] & 0xff) << 24);
+    uint32_t d1 = (c[4] & 0xff) | ((c[5] & 0xff) << 8) | ((c[6] & 0xff) << 16) | ((uint32_t)(c[7] & 0xff) << 24);
+    ((uint2*)xq_row)[chunk] = make_uint2(d0, d1);
+  } else {
+    uint32_t d = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      d |= ((uint32_t)(c[j] & 0xf) | ((uint32_t)(c[4 + j] & 0xf) << 4)) << (8 * j);
+    ((uint32_t*)xq_row)[chunk] = d;
+  }
+}
+
+__device__ __forceinline__ float block_max(float m, float* red) {
+  m = wave_max(m);
+  const int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) red[w] = m;
+  __syncthreads();
+  float r = red[0];
+#pragma unroll
+  for (int i = 1; i < kThreads / 64; ++i) r = fmaxf(r, red[i]);
+  return r;
+}
+
+// NC = 16-byte pieces (8 channels each) a thread keeps in registers; NC = 0 is
+// the any-K variant that reads the row a second time (from L2).
+template <int XDT, int ABITS, int NC>
+__global__ __launch_bounds__(kThreads) void quantize_act_kernel(
+    const void* __restrict__ X, const float* __restrict__ s_inv, int K, int64_t ldx,
+    void* __restrict__ Xq, float* __restrict__ scale) {
+  __shared__ float red[kThreads / 64];
+  const int64_t m = blockIdx.x;
+  const int nchunk = K >> 3;
+  constexpr size_t esz = (XDT == SERQ_F32) ? 4 : 2;
+  const char* row = (const char*)X + (size_t)m * (size_t)ldx * esz;
+  char* xq_row = (char*)Xq + (size_t)m * ((size_t)K * ABITS / 8);
+  constexpr float q = (float)((1 << (ABITS - 1)) - 1);
+
+  if constexpr (NC > 0) {
+    float v[NC][8];
+    float amax = 0.0f;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int chunk = threadIdx.x + c * kThreads;
+      if (chunk < nchunk) {
+        load8<XDT>(row, chunk, v[c]);
+        flatten8(s_inv, chunk, v[c]);
+        amax = absmax8(v[c], amax);
+      }
+    }
+    amax = block_max(amax, red);
+    const float sc = amax > 0.0f ? amax / q : 1.0f;
+    if (threadIdx.x == 0) scale[m] = sc;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int chunk = threadIdx.x + c * kThreads;
+      if (chunk < nchunk) quant_store8<ABITS>(v[c], sc, xq_row, chunk);
+    }
+  } else {
+    float amax = 0.0f;
+    for (int chunk = threadIdx.x; chunk < nchunk; chunk += kThreads) {
+      float v[8];
+      load8<XDT>(row, chunk, v);
+      flatten8(s_inv, chunk, v);
+      amax = absmax8(v, amax);
+    }
+    amax = block_max(amax, red);
+    const float sc = amax > 0.0f ? amax / q : 1.0f;
+    if (threadIdx.x == 0) scale[m] = sc;
+    for (int chunk = threadIdx.x; chunk < nchunk; chunk += kThreads) {
+      float v[8];
+      load8<XDT>(row, chunk, v);
+      flatten8(s_inv, chunk, v);
+      quant_store8<ABITS>(v, sc, xq_row, chunk);
+    }
+  }
+}
+
+template <int XDT, int ABITS>
+int launch_t(const void* X, const float* s_inv, int64_t M, int K, int64_t ldx, void* Xq, float* scale,
+             hipStream_t st) {
+  const int nchunk = K >> 3;
+  const int per = (nchunk + kThreads - 1) / kThreads;
+  dim3 grid((unsigned)M), block(kThreads);
+  if (per <= 1)
+    hipLaunchKernelGGL((quantize_act_kernel<XDT, ABITS, 1>), grid, block, 0, st, X, s_inv, K, ldx, Xq, scale);
+  else if (per <= 2)
+    hipLaunchKernelGGL((quantize_act_kernel<XDT, ABITS, 2>), grid, block, 0, st, X, s_inv, K, ldx, Xq, scale);
+  else if (per <= 4)
+    hipLaunchKernelGGL((quantize_act_kernel<XDT, ABITS, 4>), grid, block, 0, st, X, s_inv, K, ldx, Xq, scale);
+  else if (per <= 8)
+    hipLaunchKernelGGL((quantize_act_kernel<XDT, ABITS, 8>), grid, block, 0, st, X, s_inv, K, ldx, Xq, scale);
+  else
+    hipLaunchKernelGGL((quantize_act_kernel<XDT, ABITS, 0>), grid, block, 0, st, X, s_inv, K, ldx, Xq, scale);
+  return hipGetLastError() == hipSuccess ? SERQ_OK : SERQ_EHIP;
+}
+
+template <int XDT>
+int launch_b(const void* X, const float* s_inv, int64_t M, int K, int64_t ldx, int abits, void* Xq,
+             float* scale, hipStream_t st) {
+  return abits == 4 ? launch_t<XDT, 4>(X, s_inv, M, K, ldx, Xq, scale, st)
+                    : launch_t<XDT, 8>(X, s_inv, M, K, ldx, Xq, scale, st);
+}
+
+}  // namespace
+
+int launch_quantize_act(const void* X, int x_dtype, const float* s_inv, int64_t M, int K, int64_t ldx,
+                        int abits, void* Xq, float* scale, hipStream_t st) {
+  // the grid's x dimension carries the token index
+  for (int64_t m0 = 0; m0 < M; m0 += (1 << 30)) {
+    const int64_t mc = (M - m0) < (1 << 30) ? (M - m0) : (1 << 30);
+    const size_t esz = x_dtype == SERQ_F32 ? 4 : 2;
+    const void* Xs = (const char*)X + (size_t)m0 * (size_t)ldx * esz;
+    void* Xqs = (char*)Xq + (size_t)m0 * ((size_t)K * abits / 8);
+    int rc;
+    if (x_dtype == SERQ_F32) rc = launch_b<SERQ_F32>(Xs, s_inv, mc, K, ldx, abits, Xqs, scale + m0, st);
+    else if (x_dtype == SERQ_F16) rc = launch_b<SERQ_F16>(Xs, s_inv, mc, K, ldx, abits, Xqs, scale + m0, st);
+    else rc = launch_b<SERQ_BF16>(Xs, s_inv, mc, K, ldx, abits, Xqs, scale + m0, st);
+    if (rc != SERQ_OK) return rc;
+  }
+  return SERQ_OK;
+}
+
+}  // namespace serq

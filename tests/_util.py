@@ -1,0 +1,69 @@
+"""Shared plumbing of the parity tests: run both sides on the same seeded inputs.
+
+The oracle side and the HIP side never exchange intermediate values: each
+starts from the tensors `workloads.make_layer` drew.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+import torch
+
+import workloads
+from oracle import serq_oracle as orc
+
+TOL = {torch.float32: 1e-3, torch.bfloat16: 1e-2, torch.float16: 1e-2}
+DT = {"fp16": torch.float16, "bf16": torch.bfloat16, "fp32": torch.float32}
+
+
+def f32(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy()
+
+
+def f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().double().cpu().numpy()
+
+
+@dataclass
+class OracleLayer:
+    spec: workloads.LayerSpec
+    pk: dict
+    Xhat: torch.Tensor        # permuted activations, storage dtype, host
+    Xq: np.ndarray
+    scale: np.ndarray
+    R: Optional[np.ndarray]   # the R actually used (fp64 view of stored values) or None
+    rows: Optional[np.ndarray]  # sampled token rows (None = all)
+
+
+def oracle_layer(spec, L, R_mode: str = "random", rows=None) -> OracleLayer:
+    """Oracle-side preparation.  R_mode: 'random' (the drawn R), 'residual' (Eq. 5), 'none'."""
+    W = f32(L["W"])
+    s = L["s"].numpy() if L.get("s") is not None else None
+    pk = orc.pack_weights(W, s, spec.r)
+    Xhat = workloads.permute_channels(L["X"], pk["perm"])
+    Xs = Xhat if rows is None else Xhat[torch.as_tensor(rows)]
+    Xq, scale = orc.quantize_act(f32(Xs), pk["s_inv"], spec.abits)
+    if spec.r == 0 or R_mode == "none":
+        R = None
+    elif R_mode == "random":
+        R = f64(L["R"])
+    else:
+        R = f64(torch.from_numpy(pk["R"]).to(DT[spec.in_dtype]))   # the residual as it is stored
+    return OracleLayer(spec, pk, Xhat, Xq, scale, R, None if rows is None else np.asarray(rows))
+
+
+def assert_y_close(Y: torch.Tensor, Y64: np.ndarray, what: str = ""):
+    tol = TOL[Y.dtype]
+    g, mix = orc.rel_errors(f64(Y), Y64)
+    assert g <= tol and mix <= tol, f"{what}: max|dY|/max|Y| = {g:.3e}, mixed = {mix:.3e}, tol = {tol}"
+    return g, mix
+
+
+def ulp_close(a: np.ndarray, ref64: np.ndarray, dtype: torch.dtype, ulps: float = 1.0) -> bool:
+    """|a - ref| within `ulps` units in the last place of `dtype` at ref's magnitude (plus its subnormal step)."""
+    mant = {torch.float32: 24, torch.float16: 11, torch.bfloat16: 8}[dtype]
+    tiny = {torch.float32: 2.0 ** -149, torch.float16: 2.0 ** -24, torch.bfloat16: 2.0 ** -133}[dtype]
+    step = np.maximum(np.abs(ref64) * 2.0 ** (1 - mant), tiny)
+    return bool(np.all(np.abs(a.astype(np.float64) - ref64) <= ulps * step))

@@ -1,0 +1,350 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element.
+
+Bit-exact: packed weights, scales, permutation, activation codes, INT32
+accumulators.  Tolerance (max relative error, written below): Y within 1e-3 for
+fp32 output and 1e-2 for bf16 / fp16 output.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import serq_oracle as orc
+from paper_2603_08185_amd import binding as serq
+from tests._util import DT, assert_y_close, f32, f64, oracle_layer, ulp_close
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _small_spec(abits, M, K, N, r, in_dtype="bf16", out_dtype="bf16", n_outlier=3, seed_index=0):
+    return workloads.LayerSpec(f"t_a{abits}_M{M}_K{K}_N{N}_r{r}", 9, abits, M, K, N, r, in_dtype, out_dtype,
+                               n_outlier, 20.0, 60.0, seed_index=seed_index)
+
+
+# ---------------------------------------------------------------------------
+# quantize_act
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("abits", [4, 8])
+@pytest.mark.parametrize("dtype", ["bf16", "fp16", "fp32"])
+@pytest.mark.parametrize("M,K", [(1, 64), (7, 192), (33, 2048), (5, 4096), (3, 11008), (2, 14336), (2, 16448)])
+def test_quantize_act_bit_exact(abits, dtype, M, K):
+    spec = _small_spec(abits, M, K, 32, 0, in_dtype=dtype)
+    L = workloads.make_layer(spec, want=("X", "s"))
+    X = L["X"] if dtype != "fp32" else L["X"].float()
+    s_inv = (np.float32(1.0) / L["s"].numpy()).astype(np.float32)
+    Xq_o, scale_o = orc.quantize_act(f32(X), s_inv, abits)
+    Xq, scale = serq.quantize_act(X.to(DEV), torch.from_numpy(s_inv).to(DEV), abits)
+    got = serq.unpack_act(Xq, abits, M, K).cpu().numpy()
+    assert np.array_equal(scale.cpu().numpy().view(np.uint32), scale_o.view(np.uint32))
+    assert np.array_equal(got, Xq_o)
+    # already-flattened input: s_inv = NULL skips the multiply
+    Xq2, scale2 = serq.quantize_act(X.to(DEV), None, abits)
+    Xq_o2, scale_o2 = orc.quantize_act(f32(X), None, abits)
+    assert np.array_equal(scale2.cpu().numpy().view(np.uint32), scale_o2.view(np.uint32))
+    assert np.array_equal(serq.unpack_act(Xq2, abits, M, K).cpu().numpy(), Xq_o2)
+
+
+def test_quantize_act_edges():
+    # zero token, a tie-heavy integer row, strided rows, and M = 0
+    K = 128
+    X = torch.zeros((4, K), dtype=torch.float32)
+    X[1] = torch.arange(K, dtype=torch.float32) % 15 - 7          # integers -7..7: scale exactly 1
+    X[2] = (torch.arange(K, dtype=torch.float32) % 29 - 14) * 0.5  # halves: ties at scale 1
+    X[2, 0] = 7.0
+    X[3, 5] = -3.25
+    for abits in (4, 8):
+        Xq_o, scale_o = orc.quantize_act(X.numpy(), None, abits)
+        Xq, scale = serq.quantize_act(X.to(DEV), None, abits)
+        assert np.array_equal(scale.cpu().numpy(), scale_o)
+        assert np.array_equal(serq.unpack_act(Xq, abits, 4, K).cpu().numpy(), Xq_o)
+        assert scale_o[0] == 1.0
+    big = torch.randn((6, 2 * K), dtype=torch.bfloat16, generator=torch.Generator().manual_seed(3))
+    view = big.to(DEV)[:, :K]                                       # row stride 2K
+    Xq, scale = serq.quantize_act(view, None, 4)
+    Xq_o, scale_o = orc.quantize_act(f32(big[:, :K]), None, 4)
+    assert np.array_equal(serq.unpack_act(Xq, 4, 6, K).cpu().numpy(), Xq_o)
+    assert np.array_equal(scale.cpu().numpy(), scale_o)
+    e = torch.empty((0, K), dtype=torch.bfloat16, device=DEV)
+    Xq, scale = serq.quantize_act(e, None, 4)
+    assert scale.numel() == 0
+
+
+# ---------------------------------------------------------------------------
+# offline pack
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["fp16", "bf16", "fp32"])
+@pytest.mark.parametrize("N,K,r", [(32, 64, 16), (96, 320, 32), (256, 256, 16), (288, 1088, 128)])
+def test_pack_weights_parity(dtype, N, K, r):
+    spec = _small_spec(4, 4, K, N, r, in_dtype=dtype)
+    L = workloads.make_layer(spec, want=("W", "s"))
+    W = L["W"] if dtype != "fp32" else L["W"].float()
+    pk_o = orc.pack_weights(f32(W), L["s"].numpy(), r)
+    rdt = DT[dtype] if dtype != "fp32" else torch.bfloat16
+    pk = serq.pack_weights(W.to(DEV), L["s"].to(DEV), r, r_dtype=rdt)
+    assert np.array_equal(pk.perm.cpu().numpy(), pk_o["perm"])
+    assert np.array_equal(pk.wscale.cpu().numpy().view(np.uint32), pk_o["wscale"].view(np.uint32))
+    assert np.array_equal(pk.s_inv.cpu().numpy().view(np.uint32), pk_o["s_inv"].view(np.uint32))
+    assert np.array_equal(serq.unpack_weights(pk.Wq, N, K).cpu().numpy(), pk_o["Wq"])
+    # residual: fp32 fused multiply-add then one rounding to the storage type, against the fp64 value
+    assert ulp_close(f64(pk.R), pk_o["R"], rdt, ulps=1.0)
+    assert np.max(np.abs(f64(pk.R))) > 0
+    back = serq.unpack_lowrank(pk.Rp, N, r, rdt)
+    assert torch.equal(back.view(torch.int16), pk.R.view(torch.int16))
+    # caller-supplied order and no flattening vector
+    rng = np.random.default_rng(1)
+    perm = rng.permutation(K).astype(np.int32)
+    pk_o2 = orc.pack_weights(f32(W), None, r, perm=perm)
+    pk2 = serq.pack_weights(W.to(DEV), None, r, perm_in=torch.from_numpy(perm).to(DEV), r_dtype=rdt)
+    assert np.array_equal(pk2.perm.cpu().numpy(), perm)
+    assert np.all(pk2.s_inv.cpu().numpy() == 1.0)
+    assert np.array_equal(serq.unpack_weights(pk2.Wq, N, K).cpu().numpy(), pk_o2["Wq"])
+    assert np.array_equal(pk2.wscale.cpu().numpy(), pk_o2["wscale"])
+
+
+def test_pack_saliency_ties_and_zero_rows():
+    N, K = 32, 64
+    W = torch.zeros((N, K), dtype=torch.float32)
+    W[:, 5] = 1.0
+    W[:, 9] = 1.0          # ties with channel 5: lower index first
+    W[:, 60] = 2.0
+    W[3, :] = 0.0          # an all-zero output channel
+    pk_o = orc.pack_weights(W.numpy(), None, 16)
+    pk = serq.pack_weights(W.to(DEV), None, 16, r_dtype=torch.float16)
+    assert pk_o["perm"][:3].tolist() == [60, 5, 9]
+    assert np.array_equal(pk.perm.cpu().numpy(), pk_o["perm"])
+    assert np.array_equal(pk.wscale.cpu().numpy(), pk_o["wscale"]) and pk_o["wscale"][3] == 1.0
+    assert np.array_equal(serq.unpack_weights(pk.Wq, N, K).cpu().numpy(), pk_o["Wq"])
+
+
+def test_pack_lowrank_roundtrip():
+    for dt in (torch.float16, torch.bfloat16):
+        R = torch.randn((48, 96), generator=torch.Generator().manual_seed(5)).to(dt).to(DEV)
+        Rp = serq.pack_lowrank(R)
+        assert torch.equal(serq.unpack_lowrank(Rp, 96, 48, dt).view(torch.int16), R.view(torch.int16))
+
+
+# ---------------------------------------------------------------------------
+# integer GEMM: bit-exact accumulators on both kernels, tiles + ragged tails
+# ---------------------------------------------------------------------------
+def _codes(M, K, N, abits, seed):
+    rng = np.random.default_rng(seed)
+    q = orc.qmax(abits)
+    Xq = rng.integers(-q, q + 1, size=(M, K)).astype(np.int8)
+    Wq = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
+    # integer-valued fp32 inputs whose quantisation is the identity (row extremes present)
+    Xq[:, 0] = q
+    Wq[:, 1] = -7
+    return Xq, Wq
+
+
+def _device_codes(Xq, Wq, abits):
+    M, K = Xq.shape
+    N = Wq.shape[0]
+    pk = serq.pack_weights(torch.from_numpy(Wq.astype(np.float32)).to(DEV), None, 0,
+                           perm_in=torch.arange(K, dtype=torch.int32, device=DEV))
+    xq, scale = serq.quantize_act(torch.from_numpy(Xq.astype(np.float32)).to(DEV), None, abits)
+    assert torch.all(scale == 1.0) and torch.all(pk.wscale == 1.0)
+    return pk, xq, scale
+
+
+@pytest.mark.parametrize("abits", [4, 8])
+@pytest.mark.parametrize("M,N,K", [(1, 32, 64), (5, 96, 192), (16, 288, 448), (32, 1024, 2048), (17, 64, 8192)])
+@pytest.mark.parametrize("splitk", [0, 1, 2, 3, 7])
+def test_gemm_i32_skinny(abits, M, N, K, splitk):
+    Xq, Wq = _codes(M, K, N, abits, seed=M + N + K)
+    pk, xq, _ = _device_codes(Xq, Wq, abits)
+    want = orc.gemm_i32(Xq, Wq)
+    ws = serq.workspace(M, N, K, 0, abits, DEV)
+    if splitk > K // 64:
+        pytest.skip("split factor exceeds the number of K fragments")
+    fl = serq.flags(serq.PATH_SKINNY, splitk=splitk)
+    got = serq.gemm_i32(xq, abits, pk.Wq, M, N, K, ws=ws, flags_=fl)
+    assert np.array_equal(got.cpu().numpy(), want)
+    again = serq.gemm_i32(xq, abits, pk.Wq, M, N, K, ws=ws, flags_=fl)   # workspace left clean, result repeatable
+    assert torch.equal(got, again)
+
+
+@pytest.mark.parametrize("abits", [4, 8])
+@pytest.mark.parametrize("M,N,K", [(1, 32, 64), (40, 96, 192), (256, 256, 512), (300, 288, 448), (513, 544, 1088)])
+def test_gemm_i32_mfma(abits, M, N, K):
+    Xq, Wq = _codes(M, K, N, abits, seed=M + N + K + 1)
+    pk, xq, _ = _device_codes(Xq, Wq, abits)
+    want = orc.gemm_i32(Xq, Wq)
+    got = serq.gemm_i32(xq, abits, pk.Wq, M, N, K, flags_=serq.flags(serq.PATH_MFMA))
+    assert np.array_equal(got.cpu().numpy(), want)
+    if M <= 32:
+        sk = serq.gemm_i32(xq, abits, pk.Wq, M, N, K, ws=serq.workspace(M, N, K, 0, abits, DEV),
+                           flags_=serq.flags(serq.PATH_SKINNY))
+        assert torch.equal(sk, got)
+
+
+def test_gemm_extreme_codes_no_overflow():
+    # every product at its maximum magnitude over a long K
+    for abits in (4, 8):
+        q = orc.qmax(abits)
+        M, N, K = 33, 64, 14336
+        Xq = np.full((M, K), -q, np.int8)
+        Wq = np.full((N, K), 7, np.int8)
+        Wq[::2] = -7
+        pk, xq, _ = _device_codes(Xq, Wq, abits)
+        got = serq.gemm_i32(xq, abits, pk.Wq, M, N, K, flags_=serq.flags(serq.PATH_MFMA))
+        assert np.array_equal(got.cpu().numpy(), orc.gemm_i32(Xq, Wq))
+
+
+# ---------------------------------------------------------------------------
+# the fused layer
+# ---------------------------------------------------------------------------
+def _run_layer(spec, R_mode="random", path=serq.PATH_AUTO, rows=None, splitk=0, check_pack=True):
+    want = ("X", "s", "W", "R") if R_mode == "random" else ("X", "s", "W")
+    L = workloads.make_layer(spec, want=want)
+    O = oracle_layer(spec, L, R_mode=R_mode, rows=rows)
+    rdt = DT[spec.in_dtype]
+    pk = serq.pack_weights(L["W"].to(DEV), L["s"].to(DEV), spec.r, r_dtype=rdt)
+    assert np.array_equal(pk.perm.cpu().numpy(), O.pk["perm"])
+    if check_pack:
+        assert np.array_equal(pk.wscale.cpu().numpy(), O.pk["wscale"])
+        assert np.array_equal(serq.unpack_weights(pk.Wq, spec.N, spec.K).cpu().numpy(), O.pk["Wq"])
+    Xq, scale = serq.quantize_act(O.Xhat.to(DEV), pk.s_inv, spec.abits)
+    codes = serq.unpack_act(Xq, spec.abits, spec.M, spec.K).cpu().numpy()
+    sc = scale.cpu().numpy()
+    sel = slice(None) if rows is None else O.rows
+    assert np.array_equal(codes[sel], O.Xq)
+    assert np.array_equal(sc[sel].view(np.uint32), O.scale.view(np.uint32))
+    if R_mode == "random":
+        Rp = serq.pack_lowrank(L["R"].to(DEV))
+    elif R_mode == "residual":
+        Rp = pk.Rp
+        assert ulp_close(f64(pk.R), O.pk["R"], rdt)
+    else:
+        Rp = None
+    ws = serq.workspace(spec.M, spec.N, spec.K, spec.r, spec.abits, DEV)
+    fl = serq.flags(path, splitk=splitk)
+    acc = serq.gemm_i32(Xq, spec.abits, pk.Wq, spec.M, spec.N, spec.K, ws=ws, flags_=fl).cpu().numpy()
+    acc_o = orc.gemm_i32(O.Xq, O.pk["Wq"])
+    assert np.array_equal(acc[sel], acc_o)
+    Y = serq.linear(Xq, scale, spec.abits, pk.Wq, pk.wscale, spec.M, spec.N, spec.K, Rp=Rp,
+                    r=spec.r if Rp is not None else 0, r_dtype=rdt, out_dtype=DT[spec.out_dtype], ws=ws, flags_=fl)
+    Y64 = orc.linear(O.Xq, O.scale, O.pk["Wq"], O.pk["wscale"], O.R, acc=acc_o)
+    Ysel = Y if rows is None else Y[torch.as_tensor(O.rows, device=Y.device)]
+    errs = assert_y_close(Ysel, Y64, spec.name)
+    return Y, Y64, errs
+
+
+@pytest.mark.parametrize("R_mode", ["random", "residual", "none"])
+def test_config1_tiny(R_mode):
+    _run_layer(workloads.config1(), R_mode=R_mode)
+    _run_layer(workloads.config1(), R_mode=R_mode, path=serq.PATH_MFMA)
+
+
+@pytest.mark.parametrize("abits", [4, 8])
+@pytest.mark.parametrize("in_dtype,out_dtype", [("bf16", "bf16"), ("fp16", "fp32"), ("fp16", "fp16")])
+@pytest.mark.parametrize("M,K,N,r,path", [
+    (3, 192, 96, 16, serq.PATH_SKINNY),
+    (32, 1088, 288, 128, serq.PATH_SKINNY),
+    (40, 192, 96, 32, serq.PATH_MFMA),
+    (300, 1088, 288, 128, serq.PATH_MFMA),
+    (257, 512, 544, 64, serq.PATH_MFMA),
+])
+def test_layer_small_shapes(abits, in_dtype, out_dtype, M, K, N, r, path):
+    spec = _small_spec(abits, M, K, N, r, in_dtype=in_dtype, out_dtype=out_dtype)
+    _run_layer(spec, R_mode="random", path=path)
+    _run_layer(spec, R_mode="residual", path=path)
+
+
+def test_salient_block_offset_and_rank_zero():
+    spec = _small_spec(4, 9, 256, 64, 32)
+    L = workloads.make_layer(spec)
+    O = oracle_layer(spec, L)
+    pk = serq.pack_weights(L["W"].to(DEV), L["s"].to(DEV), spec.r)
+    Xq, scale = serq.quantize_act(O.Xhat.to(DEV), pk.s_inv, 4)
+    Rp = serq.pack_lowrank(L["R"].to(DEV))
+    for path in (serq.PATH_SKINNY, serq.PATH_MFMA):
+        fl = serq.flags(path, splitk=1)
+        Y = serq.linear(Xq, scale, 4, pk.Wq, pk.wscale, 9, 64, 256, Rp=Rp, r=32, s_begin=48, flags_=fl)
+        Y64 = orc.linear(O.Xq, O.scale, O.pk["Wq"], O.pk["wscale"], f64(L["R"]), s_begin=48)
+        assert_y_close(Y, Y64, "s_begin=48")
+        Y0 = serq.linear(Xq, scale, 4, pk.Wq, pk.wscale, 9, 64, 256, Rp=Rp, r=0, flags_=fl)
+        Yn = serq.linear(Xq, scale, 4, pk.Wq, pk.wscale, 9, 64, 256, Rp=None, r=32, flags_=fl)
+        plain = orc.linear(O.Xq, O.scale, O.pk["Wq"], O.pk["wscale"], None)
+        assert_y_close(Y0, plain, "r=0")
+        assert torch.equal(Y0, Yn)
+
+
+def test_config2_attention_projection():
+    _run_layer(workloads.config2())
+
+
+@pytest.mark.parametrize("which,M", [("up", 1), ("up", 16), ("down", 1), ("down", 16), ("up", 256), ("down", 256)])
+def test_config3_mlp_pair(which, M):
+    _run_layer(workloads.config3(which, M))
+
+
+@pytest.mark.parametrize("which", ["up", "down"])
+def test_config3_mlp_pair_M4096_sampled_rows(which):
+    # full-size launch as the benchmark times it; the oracle evaluates 96 sampled tokens completely
+    spec = workloads.config3(which, 4096)
+    rows = np.sort(np.random.default_rng(42).choice(4096, size=96, replace=False))
+    rows[0], rows[-1] = 0, 4095
+    _run_layer(spec, rows=rows, check_pack=(which == "up"))
+
+
+@pytest.mark.parametrize("M", [1, 4, 32])
+def test_config4_wide_decode(M):
+    _run_layer(workloads.config4(M), check_pack=(M == 1))
+
+
+@pytest.mark.parametrize("layer,r", [("qkv", 32), ("o", 64), ("gate_up", 128), ("down", 256), ("o", 0)])
+def test_config5_block_stack_sampled_rows(layer, r):
+    spec = workloads.config5(layer, r)
+    rows = np.sort(np.random.default_rng(7).choice(4096, size=64, replace=False))
+    rows[0], rows[-1] = 0, 4095
+    _run_layer(spec, R_mode="random" if r else "none", rows=rows, check_pack=False)
+
+
+def test_split_k_is_deterministic_and_matches_unsplit():
+    spec = workloads.config3("down", 16)
+    L = workloads.make_layer(spec)
+    O = oracle_layer(spec, L)
+    pk = serq.pack_weights(L["W"].to(DEV), L["s"].to(DEV), spec.r)
+    Xq, scale = serq.quantize_act(O.Xhat.to(DEV), pk.s_inv, spec.abits)
+    Rp = serq.pack_lowrank(L["R"].to(DEV))
+    ws = serq.workspace(spec.M, spec.N, spec.K, spec.r, spec.abits, DEV)
+    outs = []
+    for splitk in (1, 4, 8, 8, 8):
+        outs.append(serq.linear(Xq, scale, spec.abits, pk.Wq, pk.wscale, spec.M, spec.N, spec.K, Rp=Rp, r=spec.r,
+                                ws=ws, flags_=serq.flags(serq.PATH_SKINNY, splitk=splitk)))
+    assert torch.equal(outs[2], outs[3]) and torch.equal(outs[3], outs[4])
+    Y64 = orc.linear(O.Xq, O.scale, O.pk["Wq"], O.pk["wscale"], f64(L["R"]))
+    for y in outs:
+        assert_y_close(y, Y64)
+
+
+def test_error_codes():
+    L = serq.lib()
+    x = torch.zeros(64 * 64, dtype=torch.uint8, device=DEV)
+    sc = torch.ones(64, dtype=torch.float32, device=DEV)
+    y = torch.empty((64, 64), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(serq.SerqError) as e:
+        serq.linear(x, sc, 5, x, sc, 1, 64, 64, Y=y)
+    assert e.value.code == -2
+    with pytest.raises(serq.SerqError) as e:
+        serq.linear(x, sc, 4, x, sc, 1, 48, 64, Y=y)          # N not a multiple of 32
+    assert e.value.code == -3
+    with pytest.raises(serq.SerqError) as e:
+        serq.linear(x, sc, 4, x, sc, 1, 64, 96, Y=y)          # K not a multiple of 64
+    assert e.value.code == -3
+    with pytest.raises(serq.SerqError) as e:
+        serq.linear(x, sc, 4, x, sc, 1, 64, 64, Rp=x, r=24, Y=y)   # r not a multiple of 16
+    assert e.value.code == -3
+    with pytest.raises(serq.SerqError) as e:
+        serq.linear(x, sc, 4, x, sc, 40, 64, 64, Y=y, flags_=serq.flags(serq.PATH_SKINNY))  # M > 32
+    assert e.value.code == -3
+    with pytest.raises(serq.SerqError) as e:
+        serq.linear(x[1:], sc, 4, x, sc, 1, 64, 64, Y=y)      # misaligned
+    assert e.value.code == -4
+    with pytest.raises(serq.SerqError) as e:
+        serq.linear(x, sc, 4, x, sc, 1, 64, 128, Y=y, flags_=serq.flags(serq.PATH_SKINNY, splitk=2))  # no workspace
+    assert e.value.code == -5
+    assert L.serq_linear(None, None, 4, None, None, 0, 0, None, 2, 1, 64, 64, None, 2, 64, None, 0, 0, None) == -1

@@ -1,0 +1,106 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, and
+rejects bad arguments before any GPU work (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2603_08185_amd import binding as serq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "serq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(serq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_exported_and_bound():
+    names = _declared()
+    assert len(names) >= 14
+    L = serq.lib()
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in include/serq.h but not exported"
+        assert n in serq.SIGNATURES, f"{n} has no Python binding signature"
+    assert sorted(serq.SIGNATURES) == names
+
+
+def test_version_and_messages():
+    L = serq.lib()
+    assert L.serq_version() >= 100
+    for code in range(0, -8, -1):
+        assert len(L.serq_strerror(code)) > 0
+    assert b"unknown" in L.serq_strerror(-99)
+
+
+def test_size_queries():
+    L = serq.lib()
+    assert L.serq_packed_act_bytes(4096, 4096, 8) == 4096 * 4096
+    assert L.serq_packed_act_bytes(4096, 4096, 4) == 4096 * 2048
+    assert L.serq_packed_act_bytes(1, 100, 4) == 0          # K not a multiple of 64
+    assert L.serq_packed_act_bytes(1, 64, 3) == 0
+    assert L.serq_packed_weight_bytes(11008, 4096) == 11008 * 4096 // 2
+    assert L.serq_packed_weight_bytes(11000, 4096) == 0     # N not a multiple of 32
+    assert L.serq_packed_lowrank_bytes(11008, 128) == 11008 * 128 * 2
+    assert L.serq_packed_lowrank_bytes(11008, 100) == 0
+    assert L.serq_workspace_bytes(1, 11008, 4096, 128, 8) > 0
+    assert L.serq_workspace_bytes(1, 11008, 100, 128, 8) == 0
+
+
+def test_argument_validation_precedes_any_launch():
+    L = serq.lib()
+    buf = (ctypes.c_char * 4096)()
+    a = ctypes.cast(buf, ctypes.c_void_p).value
+    a = (a + 15) & ~15
+    p = ctypes.c_void_p(a)
+    # quantize_act
+    assert L.serq_quantize_act(p, 7, None, 1, 64, 64, 4, p, p, None) == -2      # dtype
+    assert L.serq_quantize_act(p, 2, None, 1, 64, 64, 5, p, p, None) == -2      # abits
+    assert L.serq_quantize_act(p, 2, None, 1, 100, 104, 4, p, p, None) == -3    # K
+    assert L.serq_quantize_act(p, 2, None, 1, 128, 64, 4, p, p, None) == -3     # ldx < K
+    assert L.serq_quantize_act(p, 2, None, 1, 64, 68, 4, p, p, None) == -4      # ldx alignment
+    assert L.serq_quantize_act(None, 2, None, 1, 64, 64, 4, p, p, None) == -1
+    assert L.serq_quantize_act(ctypes.c_void_p(a + 2), 2, None, 1, 64, 64, 4, p, p, None) == -4
+    assert L.serq_quantize_act(None, 2, None, 0, 64, 64, 4, None, None, None) == 0   # M = 0: nothing to do
+    # linear
+    args = dict(M=1, N=64, K=64)
+    def lin(Xq=p, scale=p, abits=4, Wq=p, wscale=p, s_begin=0, r=0, Rp=None, rdt=2, M=1, N=64, K=64, Y=p, ydt=2,
+            ldy=64, ws=None, wsb=0, fl=0):
+        return L.serq_linear(Xq, scale, abits, Wq, wscale, s_begin, r, Rp, rdt, M, N, K, Y, ydt, ldy, ws, wsb, fl, None)
+    assert lin(abits=6) == -2
+    assert lin(ydt=9) == -2
+    assert lin(N=48) == -3
+    assert lin(K=96) == -3
+    assert lin(K=262144) == -3
+    assert lin(r=24, Rp=p) == -3
+    assert lin(r=128, Rp=p) == -3            # s_begin + r > K
+    assert lin(s_begin=8, r=16, Rp=p) == -3
+    assert lin(r=16, Rp=p, rdt=0) == -2      # R must be a 16-bit type
+    assert lin(ldy=32) == -3
+    assert lin(ldy=68) == -4
+    assert lin(Y=None) == -1
+    assert lin(Wq=None) == -1
+    assert lin(M=64, fl=1) == -3             # skinny path forced with M > 32
+    assert lin(fl=9) == -7
+    assert lin(M=0) == 0
+    # gemm_i32
+    assert L.serq_gemm_i32(p, 4, p, 1, 64, 64, None, 64, None, 0, 0, None) == -1
+    assert L.serq_gemm_i32(p, 4, p, 1, 64, 64, p, 32, None, 0, 0, None) == -3
+    # pack
+    assert L.serq_pack_weights(None, 2, None, None, 64, 64, 0, p, p, p, p, None, 2, None, None) == -1
+    assert L.serq_pack_weights(p, 2, None, None, 64, 64, 8, p, p, p, p, None, 2, None, None) == -3
+    assert L.serq_pack_weights(p, 2, None, None, 64, 64, 16, p, p, p, p, None, 0, p, None) == -2
+    assert L.serq_pack_lowrank(p, 0, 64, 16, p, None) == -2
+    assert L.serq_unpack_weights(p, 60, 64, p, None) == -3
+    assert L.serq_unpack_act(p, 4, 1, 60, p, None) == -3
+    assert L.serq_workspace_init(None, 16, None) == -1
+    assert L.serq_workspace_init(None, 0, None) == 0
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(serq, "_lib", None)
+    monkeypatch.setattr(serq, "LIB_PATH", "/nonexistent/libserq.so")
+    with pytest.raises(ImportError):
+        serq.lib()
