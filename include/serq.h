@@ -21,7 +21,7 @@
  *   - Return value: SERQ_OK or a negative SERQ_E* code; nothing throws or
  *     aborts.  Non-finite inputs give undefined outputs, not an error.
  *   - Shape limits: K a multiple of 64, 64 <= K <= 131072; N a multiple of
- *     32; r a multiple of 16 with s_begin + r <= K, s_begin a multiple of 16.
+ *     32; r a multiple of 16 with s_begin + r <= K, s_begin a multiple of 32.
  *   - Packed tensors (Xq, Wq, Rp) have library-private layouts; use the
  *     serq_unpack_* calls to read them back in canonical form.
  */

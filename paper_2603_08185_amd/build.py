@@ -12,7 +12,7 @@ SOURCES = ["api.hip", "quantize_act.hip", "pack.hip", "skinny.hip", "gemm_mfma.h
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wno-unused-command-line-argument",
+    "-Wno-unused-command-line-argument", "-Wno-inline-asm",
 ]
 
 

@@ -22,7 +22,7 @@ __global__ __launch_bounds__(256) void zero_fill_kernel(uint32_t* p, size_t n) {
 }
 
 int check_lowrank(int64_t K, int s_begin, int r) {
-  if (r < 0 || (r % 16) != 0 || s_begin < 0 || (s_begin % 16) != 0) return SERQ_ESHAPE;
+  if (r < 0 || (r % 16) != 0 || s_begin < 0 || (s_begin % 32) != 0) return SERQ_ESHAPE;
   if ((int64_t)s_begin + r > K) return SERQ_ESHAPE;
   return SERQ_OK;
 }

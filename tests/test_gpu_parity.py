@@ -167,7 +167,8 @@ def test_gemm_i32_skinny(abits, M, N, K, splitk):
 
 
 @pytest.mark.parametrize("abits", [4, 8])
-@pytest.mark.parametrize("M,N,K", [(1, 32, 64), (40, 96, 192), (256, 256, 512), (300, 288, 448), (513, 544, 1088)])
+@pytest.mark.parametrize("M,N,K", [(1, 32, 64), (40, 96, 192), (256, 256, 512), (300, 288, 448), (513, 544, 1088),
+                                   (700, 320, 1024), (257, 32, 256), (64, 800, 2560), (33, 64, 128), (90, 160, 832)])
 def test_gemm_i32_mfma(abits, M, N, K):
     Xq, Wq = _codes(M, K, N, abits, seed=M + N + K + 1)
     pk, xq, _ = _device_codes(Xq, Wq, abits)
@@ -246,6 +247,10 @@ def test_config1_tiny(R_mode):
     (40, 192, 96, 32, serq.PATH_MFMA),
     (300, 1088, 288, 128, serq.PATH_MFMA),
     (257, 512, 544, 64, serq.PATH_MFMA),
+    (70, 320, 64, 48, serq.PATH_MFMA),
+    (130, 256, 96, 80, serq.PATH_MFMA),
+    (64, 832, 32, 16, serq.PATH_MFMA),
+    (5, 320, 64, 144, serq.PATH_SKINNY),
 ])
 def test_layer_small_shapes(abits, in_dtype, out_dtype, M, K, N, r, path):
     spec = _small_spec(abits, M, K, N, r, in_dtype=in_dtype, out_dtype=out_dtype)
@@ -262,9 +267,9 @@ def test_salient_block_offset_and_rank_zero():
     Rp = serq.pack_lowrank(L["R"].to(DEV))
     for path in (serq.PATH_SKINNY, serq.PATH_MFMA):
         fl = serq.flags(path, splitk=1)
-        Y = serq.linear(Xq, scale, 4, pk.Wq, pk.wscale, 9, 64, 256, Rp=Rp, r=32, s_begin=48, flags_=fl)
-        Y64 = orc.linear(O.Xq, O.scale, O.pk["Wq"], O.pk["wscale"], f64(L["R"]), s_begin=48)
-        assert_y_close(Y, Y64, "s_begin=48")
+        Y = serq.linear(Xq, scale, 4, pk.Wq, pk.wscale, 9, 64, 256, Rp=Rp, r=32, s_begin=96, flags_=fl)
+        Y64 = orc.linear(O.Xq, O.scale, O.pk["Wq"], O.pk["wscale"], f64(L["R"]), s_begin=96)
+        assert_y_close(Y, Y64, "s_begin=96")
         Y0 = serq.linear(Xq, scale, 4, pk.Wq, pk.wscale, 9, 64, 256, Rp=Rp, r=0, flags_=fl)
         Yn = serq.linear(Xq, scale, 4, pk.Wq, pk.wscale, 9, 64, 256, Rp=None, r=32, flags_=fl)
         plain = orc.linear(O.Xq, O.scale, O.pk["Wq"], O.pk["wscale"], None)

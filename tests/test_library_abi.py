@@ -76,7 +76,7 @@ def test_argument_validation_precedes_any_launch():
     assert lin(K=262144) == -3
     assert lin(r=24, Rp=p) == -3
     assert lin(r=128, Rp=p) == -3            # s_begin + r > K
-    assert lin(s_begin=8, r=16, Rp=p) == -3
+    assert lin(s_begin=16, r=16, Rp=p) == -3    # the salient block starts at a multiple of 32
     assert lin(r=16, Rp=p, rdt=0) == -2      # R must be a 16-bit type
     assert lin(ldy=32) == -3
     assert lin(ldy=68) == -4
