@@ -58,6 +58,8 @@ extern "C" {
 #define SERQ_FLAG_SPLITK(n) (((n) & 0xff) << 8)
 /* bits 16..19 of `flags`: token-tile group height of the MFMA path's block order (0 = auto) */
 #define SERQ_FLAG_GROUPM(n) (((n) & 0xf) << 16)
+/* bits 20..30 of `flags`: number of column tiles of the MFMA path (0 = auto; clamped to the valid range) */
+#define SERQ_FLAG_COLTILES(n) (((n) & 0x7ff) << 20)
 
 int         serq_version(void);
 const char* serq_strerror(int code);

@@ -90,8 +90,8 @@ def _dev(t: torch.Tensor, name: str):
         raise ValueError(f"{name} must be contiguous")
 
 
-def flags(path: int = PATH_AUTO, splitk: int = 0, groupm: int = 0) -> int:
-    return (path & 0xff) | ((splitk & 0xff) << 8) | ((groupm & 0xf) << 16)
+def flags(path: int = PATH_AUTO, splitk: int = 0, groupm: int = 0, coltiles: int = 0) -> int:
+    return (path & 0xff) | ((splitk & 0xff) << 8) | ((groupm & 0xf) << 16) | ((coltiles & 0x7ff) << 20)
 
 
 def workspace(M: int, N: int, K: int, r: int, abits: int, device) -> torch.Tensor:

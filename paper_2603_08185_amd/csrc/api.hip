@@ -164,6 +164,7 @@ static int linear_common(LinearArgs& a, int64_t M, int64_t N, int64_t K, int fla
   a.M = (int)M; a.N = (int)N; a.K = (int)K;
   a.splitk = (flags >> 8) & 0xff;
   a.groupm = (flags >> 16) & 0xf;
+  a.coltiles = (flags >> 20) & 0x7ff;
   const int path = flags & 0xff;
   if (path != SERQ_PATH_AUTO && path != SERQ_PATH_SKINNY && path != SERQ_PATH_MFMA) return SERQ_EUNSUPPORTED;
   if (path == SERQ_PATH_SKINNY && M > 32) return SERQ_ESHAPE;

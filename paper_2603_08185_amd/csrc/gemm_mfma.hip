@@ -3,43 +3,77 @@
 // epilogue fused in, so Y is written once (Eq. 2 + Eq. 7, first line):
 //   Y[m,n] = scale[m] * ( wscale[n] * sum_k Xq[m,k] Wq[n,k] + sum_j Xq[m,S_j] R[j,n] )
 //
-// Workgroup tile: 256 tokens x 256 output channels, 8 waves (2 along N x 4
-// along M), each wave 128 channels x 64 tokens = 4 x 2 MFMA tiles of 32x32
-// (128 accumulator registers).  The weights are the MFMA "A" operand (rows =
-// output channels) and the tokens the "B" operand (columns), so that each
-// lane ends up with runs of 4 consecutive output channels of one token -- a
-// contiguous 8-byte piece of a bf16 row of Y.
+// Workgroup: 8 waves = 2 along the output channels x 4 along the tokens.  A
+// workgroup tile is 256 tokens x up to 256 output channels (1..8 blocks of 32);
+// the host picks the number of column tiles so that the tiles fill the compute
+// units in whole rounds, and the two channel halves of a tile are dealt to the
+// waves so that every SIMD carries one wave of each half.  Each wave owns up to
+// 4 channel blocks x 2 token blocks = 8 MFMA tiles of 32x32 (128 accumulator
+// registers).  The weights are the MFMA "A" operand (rows = output channels)
+// and the tokens the "B" operand (columns), so each lane ends up with runs of 4
+// consecutive output channels of one token.
 //
-// K is consumed in tiles of 128 (8-bit activations) or 256 (4-bit) channels;
-// either way a token row of the tile is 128 bytes.  LDS holds two stages:
-//   weights : the 1-KiB fragments of the blob, unchanged (lane-linear, so the
-//             16-byte fragment reads of a wave are one contiguous KiB);
-//   tokens  : 256 rows x 128 B, the 16-byte piece c of row i stored at piece
-//             c ^ ((i >> 1) & 7), which makes both the row-wise stores and the
-//             column-wise fragment reads bank-conflict free.
-// Nibbles are widened only in registers, to 16*q (two VALU ops per dword); the
-// accumulators therefore hold 2^SH times the true sums and the epilogue folds
-// 2^-SH into wscale (exact).  After the K loop the integer accumulators are
-// converted in place to fp32 (wscale[n] * acc) and the r/16 low-rank steps are
-// accumulated on top with 32x32x16 f16/bf16 MFMAs, reading the packed R
-// fragments and the salient codes straight from global memory (L2).
+// The work of a workgroup is a sequence of tiles flowing through a ring of LDS
+// stages (3 x 48 KiB for 8-bit activations, 2 x 64 KiB for 4-bit):
+//   main tiles     : 128 (8-bit) or 256 (4-bit) input channels; a token row of
+//                    the tile is 128 bytes either way.  Weights: the 1-KiB
+//                    fragments of the packed blob, unchanged (lane-linear).
+//                    Tokens: 256 rows x 128 B, the 16-byte piece c of row i
+//                    stored at piece c ^ ((i >> 1) & 7): conflict-free reads.
+//   low-rank tiles : 64 salient channels each, appended after the main tiles:
+//                    32 KiB of packed R fragments plus the codes of the 256
+//                    tokens for those channels.
+// Tiles travel global -> LDS directly (global_load_lds_dwordx4: a lane's 16
+// bytes land at M0 + 16*lane); the swizzle is applied on the source side.  These
+// loads are issued from inline assembly and counted by hand with vmcnt, because
+// the compiler would wait for every outstanding LDS-bound load before any LDS
+// read it cannot disambiguate.  In the steady state the refill of a stage is
+// spread over the MFMA groups of one 64-channel step.
+//
+// Inside a tile the operand fragments are double-buffered in registers: the LDS
+// reads of the next 64-channel fragment are issued before the MFMAs of the
+// current one (scheduling fences keep them there).
+//
+// Nibbles are widened only in registers, to 16*q (three VALU ops per packed
+// dword); the accumulators hold 2^SH times the true sums and the epilogue folds
+// 2^-SH into wscale (exact).  After the last main tile the integer accumulators
+// are converted in place to fp32 (wscale[n] * acc) and the low-rank tiles are
+// accumulated on top with 32x32x16 f16/bf16 MFMAs.  16-bit outputs are then
+// transposed through LDS so that every store instruction writes whole 512-byte
+// row segments.
+#include <type_traits>
+
 #include "serq_device.h"
 
 namespace serq {
 namespace {
 
 constexpr int BM = 256;
-constexpr int BN = 256;
 constexpr int kThreads = 512;
+constexpr int kWaves = 8;
 
 template <int ABITS>
 struct Tile {
-  static constexpr int BK = ABITS == 8 ? 128 : 256;   // channels per K tile
-  static constexpr int CH = BK / 64;                  // weight fragments per 32 channels per K tile
-  static constexpr int W_BYTES = (BN / 32) * CH * 1024;
-  static constexpr int A_BYTES = BM * 128;
-  static constexpr int STAGE = W_BYTES + A_BYTES;
+  static constexpr int BK = ABITS == 8 ? 128 : 256;   // channels per main tile
+  static constexpr int CH = BK / 64;                  // 64-channel fragments per main tile
+  static constexpr int W_BYTES = 8 * CH * 1024;
+  static constexpr int X_BYTES = BM * 128;
+  static constexpr int STAGE = W_BYTES + X_BYTES;
+  static constexpr int NS = ABITS == 8 ? 3 : 2;       // ring depth
   static constexpr int SH = ABITS == 8 ? 4 : 8;
+  static constexpr int NLW = CH;                      // direct loads per wave and main tile: weights
+  static constexpr int NLX = 4;                       //                                      tokens
+  static constexpr int NL = NLW + NLX;
+  static constexpr int LR_R_BYTES = 8 * 4 * 1024;
+  static constexpr int LR_XROW = 64 * ABITS / 8;      // bytes of one token's 64 salient codes
+  static constexpr int LR_NLX = BM * LR_XROW / 16 / kThreads;
+  static constexpr int NL_LR = 4 + LR_NLX;
+  static constexpr int WS_OFF = NS * STAGE;           // 256 floats: the tile's weight scales
+  static constexpr int LDS_BYTES = WS_OFF + 256 * 4;
+  static_assert(LR_R_BYTES + BM * LR_XROW <= STAGE, "a low-rank tile fits a stage");
+  static_assert(NS == 2 || NL == NL_LR, "one vmcnt immediate serves both tile kinds");
+  static_assert(BM * 512 <= NS * STAGE, "the 16-bit output tile fits the ring");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
 
 struct MfmaParams {
@@ -50,6 +84,7 @@ struct MfmaParams {
   void* Y; int y_dtype; int64_t ldy;
   int32_t* acc_out; int64_t ldacc;
   int tiles_m, tiles_n, groupm;
+  int wide, nwide;        // column tiles 0..nwide-1 have `wide` blocks of 32 channels, the rest wide-1
 };
 
 // Workgroup id -> output tile.  Consecutive ids go to different XCDs (8 of
@@ -71,262 +106,531 @@ __device__ __forceinline__ void map_block(int bid, int tm, int tn, int gm, int& 
   tile_n = within / gsz;
 }
 
+// ---- direct-to-LDS loads and the hand-counted waits --------------------------
+__device__ __forceinline__ uint32_t lds_addr(const void* ptr) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)ptr;
+}
+// 16 bytes per lane: global (sbase + voff) -> LDS (lds_base_uniform + 16 * lane)
+__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base_uniform) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_base_uniform), "v"(voff), "s"(sbase) : "memory", "m0");
+}
+// all but the youngest N vector-memory operations of this wave have completed,
+// this wave's LDS reads are complete, and every wave of the workgroup has got here
+template <int N>
+__device__ __forceinline__ void wait_dma_barrier() {
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" :: "n"(N) : "memory");
+}
+__device__ __forceinline__ void fence() { __builtin_amdgcn_sched_barrier(0); }
+
+// ---- operand fragments ---------------------------------------------------------
 template <int ABITS>
-__global__ __launch_bounds__(kThreads) void serq_mfma_kernel(const MfmaParams p) {
+struct Frag {                       // one 64-channel fragment of a main tile
+  u4 w[4];                          // packed weights of the wave's channel blocks
+  u4 x[ABITS == 8 ? 4 : 2];         // tokens: 8-bit: [2*j + half], 4-bit: [j] (packed)
+};
+struct LrFrag {                     // 16 salient channels of a low-rank tile
+  u4 r[4];                          // R fragments of the wave's channel blocks
+  u2 x[2];                          // codes of the 2 token blocks (4-bit: .x only)
+};
+
+__device__ __forceinline__ v4i widen(uint32_t d0, uint32_t d1) {
+  int a, b, c, d;
+  unpack16(d0, a, b);
+  unpack16(d1, c, d);
+  return v4i{a, b, c, d};
+}
+
+template <int ABITS>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void serq_mfma_kernel(const MfmaParams p) {
   using T = Tile<ABITS>;
   constexpr int CH = T::CH;
-  __shared__ __align__(16) uint8_t lds[2 * T::STAGE];
+  constexpr int NS = T::NS;
+  constexpr int STAGE = T::STAGE;
+  __shared__ __align__(16) uint8_t lds[T::LDS_BYTES];
 
   const int tid = threadIdx.x;
   const int w = tid >> 6, l = tid & 63;
-  const int wn = w & 1, wm = w >> 1;
+  const int wn = (w ^ (w >> 2)) & 1;                 // every SIMD gets one wave of each channel half
+  const int wm = w >> 1;
   const int lm = l & 31, g = l >> 5;
-
   int tile_m, tile_n;
   map_block(blockIdx.x, p.tiles_m, p.tiles_n, p.groupm, tile_m, tile_n);
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-  const int nb0 = n0 >> 5;
-  const int NB = p.N >> 5;
+  const int m0 = tile_m * BM;
+  const int nbt = tile_n < p.nwide ? p.wide : p.wide - 1;                       // blocks of 32 channels in this tile
+  const int nb0 = tile_n < p.nwide ? tile_n * p.wide : p.nwide * p.wide + (tile_n - p.nwide) * (p.wide - 1);
+  const int n0 = nb0 << 5;
+  const int half = (nbt + 1) >> 1;
+  const int blk0 = __builtin_amdgcn_readfirstlane(wn ? half : 0);              // this wave's first block in the tile
+  const int nbw = __builtin_amdgcn_readfirstlane(wn ? nbt - half : half);      // and how many it owns (0..4)
   const int KB = p.K >> 6;
-  const int KT = (KB + CH - 1) / CH;
-  const size_t rowbytes = (size_t)p.K * ABITS / 8;
+  const uint32_t rowbytes = (uint32_t)p.K * ABITS / 8;
+  const int mrows = p.M - m0 < BM ? p.M - m0 : BM;   // valid token rows of this tile
 
-  // ---- global -> register -> LDS staging assignments ------------------------
-  // tokens: 4 pieces of 16 B per thread; 8 consecutive threads cover one 128-B row
-  const int a_c = tid & 7;
-  const uint8_t* a_src[4];
-  int a_dst[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = (tid >> 3) + 64 * i;
-    int gm = m0 + row;
-    gm = gm < p.M ? gm : p.M - 1;                        // rows past M are never stored
-    a_src[i] = p.Xq + (size_t)gm * rowbytes;
-    a_dst[i] = T::W_BYTES + row * 128 + 16 * (a_c ^ ((row >> 1) & 7));
-  }
-  // weights: CH pieces per thread, a straight copy of 8*CH KiB of blob fragments
-  const u4* w_src[CH];
-  bool w_ok[CH];
-  int w_ch[CH];
-#pragma unroll
-  for (int i = 0; i < CH; ++i) {
-    const int q = tid + kThreads * i;
-    const int nbl = q / (64 * CH);
-    const int within = q % (64 * CH);
-    w_ch[i] = within >> 6;
-    w_ok[i] = (nb0 + nbl) < NB;
-    const int nbc = w_ok[i] ? nb0 + nbl : NB - 1;
-    w_src[i] = p.Wq + ((size_t)nbc * KB) * 64 + within;
-  }
+  const int KTF = KB / CH;                           // full main tiles
+  const int KTAIL = KB - KTF * CH;                   // fragments of a last, partial main tile
+  const int KT = KTF + (KTAIL ? 1 : 0);
+  const int JB = (p.acc_out == nullptr) ? (p.r >> 4) : 0;
+  const int LT = (JB + 3) >> 2;                      // low-rank tiles of up to 4 x 16 channels
+  const int TT = KT + LT;
 
-  u4 ra[4];
-  u4 rw[CH];
-  auto gload = [&](int kt) {
-    size_t aoff = (size_t)kt * 128 + 16 * a_c;
-    if (aoff + 16 > rowbytes) aoff = 0;                  // K tail: stay inside the row (the weights there are zero)
+  // the tile's weight scales, times 2^-SH (exact), for the int -> float conversion
+  constexpr float kInv = 1.0f / (float)(1 << T::SH);
+  float* lws = reinterpret_cast<float*>(lds + T::WS_OFF);
+  if (tid < 256 && p.wscale != nullptr) lws[tid] = tid < 32 * nbt ? p.wscale[n0 + tid] * kInv : 0.0f;
+
+  const int wu = __builtin_amdgcn_readfirstlane(w);
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_addr(lds));
+
+  // ---- per-lane source offsets of the direct loads ------------------------------
+  // weights: wave w fetches fragments f = 8*i + w of the stage, f = nbl*CH + ch
+  uint32_t wv[T::NLW];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) ra[i] = *(const u4*)(a_src[i] + aoff);
+  for (int i = 0; i < T::NLW; ++i) {
+    const int f = i * kWaves + wu;
+    int nbl = f / CH;
+    nbl = nbl < nbt ? nbl : nbt - 1;                 // blocks past the tile: duplicates, never read
+    wv[i] = (uint32_t)((nbl * KB + (f % CH)) * 1024 + l * 16);
+  }
+  // tokens: LDS piece pc = 512*i + tid -> row pc/8, slot pc%8 holds global piece slot ^ swizzle(row)
+  uint32_t xv[T::NLX];
 #pragma unroll
-    for (int i = 0; i < CH; ++i) {
-      const bool ok = w_ok[i] && (kt * CH + w_ch[i]) < KB;
-      rw[i] = u4{0u, 0u, 0u, 0u};
-      if (ok) rw[i] = w_src[i][(size_t)kt * CH * 64];
+  for (int i = 0; i < T::NLX; ++i) {
+    const int pc = i * kThreads + tid;
+    int row = pc >> 3;
+    const int c = (pc & 7) ^ ((row >> 1) & 7);
+    row = row < mrows ? row : mrows - 1;             // rows past M: duplicates, never stored
+    xv[i] = (uint32_t)row * rowbytes + 16u * c;
+  }
+  const uint8_t* wbase = (const uint8_t*)p.Wq + (size_t)nb0 * KB * 1024;
+  const uint8_t* xbase = p.Xq + (size_t)m0 * rowbytes;
+
+  // k-th direct load of main tile t into stage st (k < NL)
+  auto issue_main_one = [&](int t, int st, int k) {
+    const uint32_t sb = lds0 + (uint32_t)st * STAGE + (uint32_t)wu * 1024;
+    if (k < T::NLW) dma16(wbase + (size_t)t * CH * 1024, wv[k], sb + kWaves * 1024 * k);
+    else dma16(xbase + (size_t)t * 128, xv[k - T::NLW], sb + T::W_BYTES + kWaves * 1024 * (k - T::NLW));
+  };
+  // a main tile whose fragments / pieces may run past K: clamp them into the tile's first fragment
+  auto issue_main_tail = [&](int t, int st) {
+    const uint32_t sb = lds0 + (uint32_t)st * STAGE + (uint32_t)wu * 1024;
+    const int nf = KB - t * CH;                      // 1 .. CH-1 valid fragments
+#pragma unroll
+    for (int i = 0; i < T::NLW; ++i) {
+      const int f = i * kWaves + wu;
+      int nbl = f / CH, ch = f % CH;
+      nbl = nbl < nbt ? nbl : nbt - 1;
+      ch = ch < nf ? ch : 0;
+      dma16(wbase + (size_t)t * CH * 1024, (uint32_t)((nbl * KB + ch) * 1024 + l * 16), sb + kWaves * 1024 * i);
+    }
+    const int npc = nf * (ABITS == 8 ? 4 : 2);       // valid 16-byte pieces of a token row
+#pragma unroll
+    for (int i = 0; i < T::NLX; ++i) {
+      const int pc = i * kThreads + tid;
+      int row = pc >> 3;
+      int c = (pc & 7) ^ ((row >> 1) & 7);
+      c = c < npc ? c : 0;
+      row = row < mrows ? row : mrows - 1;
+      dma16(xbase + (size_t)t * 128, (uint32_t)row * rowbytes + 16u * c, sb + T::W_BYTES + kWaves * 1024 * i);
     }
   };
-  auto lstore = [&](int buf) {
-    uint8_t* base = lds + buf * T::STAGE;
+  // low-rank tile lt (4 x 16 salient channels) into stage st
+  auto issue_lr = [&](int lt, int st) {
+    const uint32_t sb = lds0 + (uint32_t)st * STAGE + (uint32_t)wu * 1024;
+    const int njb = JB - 4 * lt < 4 ? JB - 4 * lt : 4;
+    const uint8_t* rbase = (const uint8_t*)p.Rp + ((size_t)nb0 * JB + 4 * lt) * 1024;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) *(u4*)(base + a_dst[i]) = ra[i];
+    for (int i = 0; i < 4; ++i) {
+      const int f = i * kWaves + wu;                 // f = nbl*4 + jbl
+      int nbl = f >> 2, jbl = f & 3;
+      nbl = nbl < nbt ? nbl : nbt - 1;
+      jbl = jbl < njb ? jbl : 0;
+      dma16(rbase, (uint32_t)((nbl * JB + jbl) * 1024 + l * 16), sb + kWaves * 1024 * i);
+    }
+    if constexpr (ABITS == 8) {
+      const uint8_t* cbase = xbase + p.s_begin + 64 * lt;
 #pragma unroll
-    for (int i = 0; i < CH; ++i) *(u4*)(base + (tid + kThreads * i) * 16) = rw[i];
+      for (int i = 0; i < 2; ++i) {
+        int row = (tid + kThreads * i) >> 2;
+        int c = (tid & 3) ^ ((row >> 2) & 3);
+        c = (64 * lt + 16 * c + 16 <= p.r) ? c : 0;  // a piece past the salient block is never read
+        row = row < mrows ? row : mrows - 1;
+        dma16(cbase, (uint32_t)row * rowbytes + 16u * c, sb + T::LR_R_BYTES + kWaves * 1024 * i);
+      }
+    } else {
+      const uint8_t* cbase = xbase + ((p.s_begin + 64 * lt) >> 1);
+      int row = tid >> 1;
+      int c = (tid & 1) ^ ((row >> 3) & 1);
+      c = (64 * lt + 32 * c < p.r) ? c : 0;
+      row = row < mrows ? row : mrows - 1;
+      dma16(cbase, (uint32_t)row * rowbytes + 16u * c, sb + T::LR_R_BYTES);
+    }
+  };
+  auto issue = [&](int t, int st) {                  // whole tile t of the sequence
+    if (t < KTF) {
+#pragma unroll
+      for (int k = 0; k < T::NL; ++k) issue_main_one(t, st, k);
+    } else if (t < KT) {
+      issue_main_tail(t, st);
+    } else {
+      issue_lr(t - KT, st);
+    }
   };
 
-  v16i acc[4][2];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
-
-  // fragment read offsets inside a stage
-  int xrow_off[2], xswz[2];
+  // ---- per-lane offsets of the fragment reads -----------------------------------
+  const int wfrag_off = (blk0 * CH * 64 + l) * 16;
+  const int lr_r_off = (blk0 * 4 * 64 + l) * 16;
+  int xrow_off[2], xswz[2], lr_x_off[2], lr_x_swz[2];
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const int row = 64 * wm + 32 * j + lm;
     xrow_off[j] = T::W_BYTES + row * 128;
     xswz[j] = (row >> 1) & 7;
+    lr_x_off[j] = T::LR_R_BYTES + row * T::LR_XROW;
+    lr_x_swz[j] = ABITS == 8 ? ((row >> 2) & 3) : ((row >> 3) & 1);
   }
-  const int wfrag_off = (4 * wn * CH * 64 + l) * 16;
 
-  gload(0);
-  lstore(0);
-  __syncthreads();
-
-  for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < KT) gload(kt + 1);
-    const uint8_t* base = lds + cur * T::STAGE;
+  auto load_frags = [&](const uint8_t* st, int ch, Frag<ABITS>& f) {
 #pragma unroll
-    for (int ch = 0; ch < CH; ++ch) {
-      v4i wa[4][2], xb[2][2];
+    for (int i = 0; i < 4; ++i) f.w[i] = *(const u4*)(st + wfrag_off + (i * CH + ch) * 1024);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const u4 wp = *(const u4*)(base + wfrag_off + (i * CH + ch) * 1024);
-        unpack_frag(wp, wa[i][0], wa[i][1]);
+    for (int j = 0; j < 2; ++j) {
+      if constexpr (ABITS == 8) {
+        const int c = 4 * ch + 2 * g;
+        f.x[2 * j] = *(const u4*)(st + xrow_off[j] + 16 * (c ^ xswz[j]));
+        f.x[2 * j + 1] = *(const u4*)(st + xrow_off[j] + 16 * ((c + 1) ^ xswz[j]));
+      } else {
+        const int c = 2 * ch + g;
+        f.x[j] = *(const u4*)(st + xrow_off[j] + 16 * (c ^ xswz[j]));
       }
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        if constexpr (ABITS == 8) {
-          const int c = 4 * ch + 2 * g;
-          xb[j][0] = as_v4i(*(const u4*)(base + xrow_off[j] + 16 * (c ^ xswz[j])));
-          xb[j][1] = as_v4i(*(const u4*)(base + xrow_off[j] + 16 * ((c + 1) ^ xswz[j])));
-        } else {
-          const int c = 2 * ch + g;
-          const u4 xp = *(const u4*)(base + xrow_off[j] + 16 * (c ^ xswz[j]));
-          unpack_frag(xp, xb[j][0], xb[j][1]);
-        }
-      }
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wa[i][t], xb[j][t], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < KT) lstore(cur ^ 1);
-    __syncthreads();
-  }
+  };
+  auto load_lr_frags = [&](const uint8_t* st, int jb4, LrFrag& f) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f.r[i] = *(const u4*)(st + lr_r_off + (i * 4 + jb4) * 1024);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      if constexpr (ABITS == 8) {
+        f.x[j] = *(const u2*)(st + lr_x_off[j] + 16 * (jb4 ^ lr_x_swz[j]) + 8 * g);
+      } else {
+        f.x[j].x = *(const uint32_t*)(st + lr_x_off[j] + 16 * ((jb4 >> 1) ^ lr_x_swz[j]) + 8 * (jb4 & 1) + 4 * g);
+        f.x[j].y = 0;
+      }
+    }
+  };
 
-  // ---- epilogue ---------------------------------------------------------------
-  // register e of lane l in tile (i,j): channel n0 + 128*wn + 32*i + 8*(e/4) + 4*g + e%4,
-  //                                     token   m0 + 64*wm + 32*j + lm.
-  const int nbase = n0 + 128 * wn + 4 * g;
-  const int mbase = m0 + 64 * wm + lm;
-
-  if (p.acc_out) {
+  // Everything from here on is specialised on the number of channel blocks this wave owns, so that
+  // the MFMA groups carry no run-time tests.  Both halves of a tile run the same sequence of
+  // barriers whatever their block counts.
+  auto body = [&](auto nbw_c) {
+    constexpr int NBW = decltype(nbw_c)::value;
+    v16i acc[4][2];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int m = mbase + 32 * j;
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const int n = nbase + 32 * i + 8 * q4;
-          if (m < p.M && n < p.N) {
-            int4 o;
-            o.x = acc[i][j][4 * q4 + 0] >> T::SH;
-            o.y = acc[i][j][4 * q4 + 1] >> T::SH;
-            o.z = acc[i][j][4 * q4 + 2] >> T::SH;
-            o.w = acc[i][j][4 * q4 + 3] >> T::SH;
-            *(int4*)(p.acc_out + (size_t)m * p.ldacc + n) = o;
-          }
-        }
-      }
-    return;
-  }
-
-  v16f accf[4][2];
-  constexpr float kInv = 1.0f / (float)(1 << T::SH);
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      const int n = nbase + 32 * i + 8 * q4;
-      float4 ws = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (n < p.N) ws = *(const float4*)(p.wscale + n);
-      const float s4[4] = {ws.x * kInv, ws.y * kInv, ws.z * kInv, ws.w * kInv};
-#pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) accf[i][j][4 * q4 + e] = s4[e] * (float)acc[i][j][4 * q4 + e];
-    }
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
 
-  if (p.r > 0) {
-    const int JB = p.r >> 4;
-    const bool bf = p.r_dtype == SERQ_BF16;
-    const u4* rsrc[4];
+    // the 16 (or fewer) MFMAs of one 64-channel fragment; REFILL: spread the NL direct
+    // loads of main tile `rt` into stage `rst` over the 8 groups
+    auto mfma_frag = [&](auto refill_c, const Frag<ABITS>& f, int rt, int rst) {
+      constexpr bool REFILL = decltype(refill_c)::value;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      int nb = nb0 + 4 * wn + i;
-      nb = nb < NB ? nb : NB - 1;
-      rsrc[i] = p.Rp + (size_t)nb * JB * 64 + l;
-    }
-    const uint8_t* xsrc[2];
+      for (int t = 0; t < 2; ++t) {
+        v4i xb[2];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      int gm = mbase + 32 * j;
-      gm = gm < p.M ? gm : p.M - 1;
-      xsrc[j] = p.Xq + (size_t)gm * rowbytes + (((size_t)p.s_begin + 8 * g) * ABITS / 8);
-    }
-    u4 rf[4];
-    u2 xc[2];
-    auto lr_load = [&](int jb) {
+        for (int j = 0; j < 2; ++j) {
+          if constexpr (ABITS == 8) xb[j] = as_v4i(f.x[2 * j + t]);
+          else xb[j] = t == 0 ? widen(f.x[j].x, f.x[j].y) : widen(f.x[j].z, f.x[j].w);
+        }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) rf[i] = rsrc[i][(size_t)jb * 64];
+        for (int i = 0; i < 4; ++i) {
+          if (i < NBW) {
+            const v4i wa = t == 0 ? widen(f.w[i].x, f.w[i].y) : widen(f.w[i].z, f.w[i].w);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        if constexpr (ABITS == 8) xc[j] = *(const u2*)(xsrc[j] + jb * 16);
-        else { xc[j].x = *(const uint32_t*)(xsrc[j] + jb * 8); xc[j].y = 0; }
+            for (int j = 0; j < 2; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wa, xb[j], acc[i][j], 0, 0, 0);
+          }
+          if constexpr (REFILL) {
+            const int gi = t * 4 + i;
+#pragma unroll
+            for (int k = 0; k < T::NL; ++k)
+              if (k * 8 / T::NL == gi) issue_main_one(rt, rst, k);
+          }
+          fence();
+        }
       }
     };
-    lr_load(0);
-    for (int jb = 0; jb < JB; ++jb) {
-      u4 rcur[4];
-      u4 xf[2];
+
+    // ---- prologue: fill the ring ---------------------------------------------------
 #pragma unroll
-      for (int i = 0; i < 4; ++i) rcur[i] = rf[i];
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        int c[8];
-        if constexpr (ABITS == 8) codes_from_a8(xc[j].x, xc[j].y, c);
-        else codes_from_a4(xc[j].x, c);
-        xf[j] = codes8_to_16bit(c, bf);
+    for (int s = 0; s < NS; ++s)
+      if (s < TT) issue(s, s);
+    if (NS == 3 && TT >= 3) wait_dma_barrier<2 * T::NL>();
+    else wait_dma_barrier<0>();
+
+    int t = 0;                                          // tile being computed
+    int st = 0;                                         // its stage
+    Frag<ABITS> F[2];
+    auto stage_ptr = [&](int s) { return (const uint8_t*)lds + s * STAGE; };
+    // Tile t has been read completely (its last fragment is in registers): make sure tile
+    // t+1 is in LDS and let every wave catch up; after that stage `st` may be refilled.
+    auto handoff_wait = [&]() {
+      if (t + 1 < TT) {
+        if (NS == 3 && t + 2 < TT) wait_dma_barrier<T::NL>();
+        else wait_dma_barrier<0>();
       }
-      if (jb + 1 < JB) lr_load(jb + 1);
+    };
+    auto advance = [&]() {
+      st = st + 1 == NS ? 0 : st + 1;
+      ++t;
+    };
+    auto prefetch_first = [&]() {                       // first fragment of main tile t (already advanced)
+      if (t < KT) load_frags(stage_ptr(st), 0, F[0]);
+    };
+
+    load_frags(stage_ptr(0), 0, F[0]);
+
+    // steady state: full main tiles whose refill (tile t+NS) is another full main tile
+    for (; t + NS < KTF; ) {
+#pragma unroll
+      for (int ch = 0; ch < CH; ++ch) {
+        if (ch + 1 < CH) {
+          load_frags(stage_ptr(st), ch + 1, F[(ch + 1) & 1]);
+          fence();
+          mfma_frag(std::false_type{}, F[ch & 1], 0, 0);
+        } else {
+          handoff_wait();
+          const int rt = t + NS, rst = st;
+          advance();
+          load_frags(stage_ptr(st), 0, F[0]);
+          fence();
+          mfma_frag(std::true_type{}, F[ch & 1], rt, rst);
+        }
+      }
+    }
+    // remaining full main tiles
+    for (; t < KTF; ) {
+#pragma unroll
+      for (int ch = 0; ch < CH; ++ch) {
+        if (ch + 1 < CH) {
+          load_frags(stage_ptr(st), ch + 1, F[(ch + 1) & 1]);
+        } else {
+          handoff_wait();
+          if (t + NS < TT) issue(t + NS, st);
+          advance();
+          prefetch_first();
+        }
+        fence();
+        mfma_frag(std::false_type{}, F[ch & 1], 0, 0);
+      }
+    }
+    if (KTAIL) {                                        // last main tile with 1 .. CH-1 fragments
+#pragma unroll
+      for (int ch = 0; ch < CH - 1; ++ch) {
+        if (ch < KTAIL) {
+          if (ch + 1 < KTAIL) {
+            load_frags(stage_ptr(st), ch + 1, F[(ch + 1) & 1]);
+          } else {
+            handoff_wait();
+            if (t + NS < TT) issue(t + NS, st);
+            advance();
+            prefetch_first();
+          }
+          fence();
+          mfma_frag(std::false_type{}, F[ch & 1], 0, 0);
+        }
+      }
+    }
+
+    // ---- epilogue ---------------------------------------------------------------
+    // register e of lane l in tile (i,j): channel n0 + 32*(blk0+i) + 8*(e/4) + 4*g + e%4,
+    //                                     token   m0 + 64*wm + 32*j + lm.
+    const int mbase = m0 + 64 * wm + lm;
+
+    if (p.acc_out) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-          if (bf)
-            accf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, rcur[i]),
-                                                                 __builtin_bit_cast(v8bf, xf[j]), accf[i][j], 0, 0, 0);
-          else
-            accf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, rcur[i]),
-                                                                __builtin_bit_cast(v8h, xf[j]), accf[i][j], 0, 0, 0);
-        }
-    }
-  }
-
+          const int m = mbase + 32 * j;
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int m = mbase + 32 * j;
-    if (m >= p.M) continue;
-    const float sm = p.scale[m];
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const int n = n0 + 32 * (blk0 + i) + 8 * q4 + 4 * g;
+            if (m < p.M && i < NBW && blk0 + i < nbt) {
+              int4 o;
+              o.x = acc[i][j][4 * q4 + 0] >> T::SH;
+              o.y = acc[i][j][4 * q4 + 1] >> T::SH;
+              o.z = acc[i][j][4 * q4 + 2] >> T::SH;
+              o.w = acc[i][j][4 * q4 + 3] >> T::SH;
+              *(int4*)(p.acc_out + (size_t)m * p.ldacc + n) = o;
+            }
+          }
+        }
+      return;
+    }
+
+    v16f accf[4][2];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        const int n = nbase + 32 * i + 8 * q4;
-        if (n >= p.N) continue;
-        const float y0 = sm * accf[i][j][4 * q4 + 0], y1 = sm * accf[i][j][4 * q4 + 1];
-        const float y2 = sm * accf[i][j][4 * q4 + 2], y3 = sm * accf[i][j][4 * q4 + 3];
-        const size_t o = (size_t)m * p.ldy + n;
-        if (p.y_dtype == SERQ_BF16) {
-          *(u2*)((uint16_t*)p.Y + o) = u2{f32x2_to_bf16x2(y0, y1), f32x2_to_bf16x2(y2, y3)};
-        } else if (p.y_dtype == SERQ_F16) {
-          *(u2*)((uint16_t*)p.Y + o) = u2{f32x2_to_f16x2(y0, y1), f32x2_to_f16x2(y2, y3)};
-        } else {
-          *(float4*)((float*)p.Y + o) = make_float4(y0, y1, y2, y3);
+        const int cl = 32 * (blk0 + i) + 8 * q4 + 4 * g;          // channel within the tile
+        const float4 ws = *(const float4*)(lws + (cl < 256 ? cl : 0));
+        const float s4[4] = {ws.x, ws.y, ws.z, ws.w};
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) accf[i][j][4 * q4 + e] = s4[e] * (float)acc[i][j][4 * q4 + e];
+      }
+
+    // low-rank tiles: the last one may hold fewer than 4 blocks of 16 channels
+    const bool bf = p.r_dtype == SERQ_BF16;
+    auto mfma_lr = [&](const LrFrag& f) {
+      u4 xf[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        int c[8];
+        if constexpr (ABITS == 8) codes_from_a8(f.x[j].x, f.x[j].y, c);
+        else codes_from_a4(f.x[j].x, c);
+        xf[j] = codes8_to_16bit(c, bf);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (i < NBW) {
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            if (bf)
+              accf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, f.r[i]),
+                                                                   __builtin_bit_cast(v8bf, xf[j]), accf[i][j], 0, 0, 0);
+            else
+              accf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, f.r[i]),
+                                                                  __builtin_bit_cast(v8h, xf[j]), accf[i][j], 0, 0, 0);
+          }
         }
       }
+    };
+    // low-rank tiles; during them every refill is another low-rank tile
+    fence();
+    for (int lt = 0; lt < LT; ++lt) {
+      const int njb = (JB - 4 * lt) < 4 ? (JB - 4 * lt) : 4;
+      for (int jb4 = 0; jb4 < njb; ++jb4) {
+        LrFrag G;
+        load_lr_frags(stage_ptr(st), jb4, G);
+        fence();
+        mfma_lr(G);
+        fence();
+      }
+      handoff_wait();
+      if (t + NS < TT) issue_lr(t + NS - KT, st);
+      advance();
+    }
+
+    if (p.y_dtype == SERQ_F32) {
+      // fp32 rows do not fit the LDS transpose: 16-byte stores straight from the accumulators
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int m = mbase + 32 * j;
+        if (m >= p.M) continue;
+        const float sm = p.scale[m];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          if (i >= NBW || blk0 + i >= nbt) continue;
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const int n = n0 + 32 * (blk0 + i) + 8 * q4 + 4 * g;
+            *(float4*)((float*)p.Y + (size_t)m * p.ldy + n) =
+                make_float4(sm * accf[i][j][4 * q4 + 0], sm * accf[i][j][4 * q4 + 1], sm * accf[i][j][4 * q4 + 2],
+                            sm * accf[i][j][4 * q4 + 3]);
+          }
+        }
+      }
+      return;
+    }
+
+    // 16-bit output: y = scale[m] * accf, cast, transpose through LDS (rows of 512 B; the 16-byte
+    // piece pc of row r sits at piece pc ^ (r & 31)), then whole-row-segment stores
+    __syncthreads();                                    // every wave is done with the ring
+    const bool ybf = p.y_dtype == SERQ_BF16;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int r = 64 * wm + 32 * j + lm;
+      const int m = m0 + r;
+      const float sm = p.scale[m < p.M ? m : p.M - 1];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (i >= NBW) continue;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int pc = 4 * (blk0 + i) + q4;
+          const float y0 = sm * accf[i][j][4 * q4 + 0], y1 = sm * accf[i][j][4 * q4 + 1];
+          const float y2 = sm * accf[i][j][4 * q4 + 2], y3 = sm * accf[i][j][4 * q4 + 3];
+          u2 o;
+          if (ybf) o = u2{f32x2_to_bf16x2(y0, y1), f32x2_to_bf16x2(y2, y3)};
+          else o = u2{f32x2_to_f16x2(y0, y1), f32x2_to_f16x2(y2, y3)};
+          *(u2*)(lds + r * 512 + 16 * (pc ^ (r & 31)) + 8 * g) = o;
+        }
+      }
+    }
+    __syncthreads();
+    const int npc = 4 * nbt;                            // 16-byte pieces of an output row segment
+#pragma unroll 4
+    for (int rr = 0; rr < BM / 16; ++rr) {
+      const int r = rr * 16 + (tid >> 5);
+      const int pc = tid & 31;
+      if (r < mrows && pc < npc) {
+        const u4 v = *(const u4*)(lds + r * 512 + 16 * (pc ^ (r & 31)));
+        *(u4*)((uint16_t*)p.Y + (size_t)(m0 + r) * p.ldy + n0 + 8 * pc) = v;
+      }
+    }
+
+  };
+  switch (nbw) {
+    case 4: body(std::integral_constant<int, 4>{}); break;
+    case 3: body(std::integral_constant<int, 3>{}); break;
+    case 2: body(std::integral_constant<int, 2>{}); break;
+    default: body(std::integral_constant<int, 1>{}); break;   // a wave without blocks computes a duplicate it never stores
   }
+}
+
+// Column tiling: C tiles of `wide` or wide-1 blocks of 32 channels.  Estimated time of a launch:
+// tiles are dealt to the compute units round by round, a round costs as much as its widest tile,
+// and a tile of b blocks costs b + kFixed (the token panel and the per-step overheads do not
+// shrink with the tile).
+void plan_columns(int tiles_m, int NB, int ncu, int& C_out, int& wide_out, int& nwide_out) {
+  const float kFixed = 4.0f;
+  float best = 0.0f;
+  int bestC = 0;
+  const int cmin = (NB + 7) / 8;
+  for (int C = cmin; C <= NB; ++C) {
+    const int wide = (NB + C - 1) / C;
+    const int nwide = NB - C * (wide - 1);            // tiles with `wide` blocks (the first ones)
+    const long long tiles = (long long)tiles_m * C;
+    const long long wide_tiles = (long long)tiles_m * nwide;
+    const long long rounds = (tiles + ncu - 1) / ncu;
+    const long long wide_rounds = (wide_tiles + ncu - 1) / ncu;
+    const float cost = wide_rounds * (wide + kFixed) + (rounds - wide_rounds) * (wide - 1 + kFixed);
+    if (bestC == 0 || cost < best - 1e-6f) { best = cost; bestC = C; }
+    if (wide <= 2) break;                             // narrower tiles only add overhead
+  }
+  C_out = bestC;
+  wide_out = (NB + bestC - 1) / bestC;
+  nwide_out = NB - bestC * (wide_out - 1);
 }
 
 }  // namespace
 
 int launch_mfma(const LinearArgs& a, hipStream_t st) {
+  static int ncu = 0;
+  if (ncu == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    ncu = n;
+  }
   MfmaParams p;
   p.Xq = a.Xq; p.scale = a.scale; p.Wq = a.Wq; p.wscale = a.wscale;
   p.Rp = a.Rp; p.r_dtype = a.r_dtype; p.s_begin = a.s_begin; p.r = a.Rp ? a.r : 0;
@@ -334,7 +638,14 @@ int launch_mfma(const LinearArgs& a, hipStream_t st) {
   p.Y = a.Y; p.y_dtype = a.y_dtype; p.ldy = a.ldy;
   p.acc_out = a.acc_out; p.ldacc = a.ldacc;
   p.tiles_m = (a.M + BM - 1) / BM;
-  p.tiles_n = (a.N + BN - 1) / BN;
+  plan_columns(p.tiles_m, a.N / 32, ncu, p.tiles_n, p.wide, p.nwide);
+  if (a.coltiles > 0) {                               // caller's override of the column tiling
+    const int NB = a.N / 32;
+    int C = a.coltiles < (NB + 7) / 8 ? (NB + 7) / 8 : (a.coltiles > NB ? NB : a.coltiles);
+    p.tiles_n = C;
+    p.wide = (NB + C - 1) / C;
+    p.nwide = NB - C * (p.wide - 1);
+  }
   p.groupm = a.groupm > 0 ? a.groupm : 4;
   const long long tiles = (long long)p.tiles_m * p.tiles_n;
   if (tiles > 0x7fffffffLL) return SERQ_ESHAPE;
