@@ -157,7 +157,10 @@ struct LinearArgs {
   void* Y; int y_dtype; int64_t ldy;
   int32_t* acc_out; int64_t ldacc;      // non-NULL: store raw accumulators instead of Y
   void* workspace; size_t workspace_bytes;
-  int splitk; int groupm; int coltiles;
+  int splitk; int groupm; int coltiles; int skinny_waves;
+#ifdef SERQ_SKINNY_DBG
+  void* dbg;
+#endif
 };
 
 int skinny_splitk_auto(int M, int N, int K);
