@@ -12,9 +12,14 @@ Prints ONE JSON line.  `value` is 2*M*N*K / step time in TOPS.  `roofline`
 prices the dominant kernel (serq_linear) against the int8 MFMA peak using its
 own launch durations, measured with HIP events on the launch stream inside the
 timed region.  `decode` reports the M = 1 weight-streaming kernel in GB/s with
-the weight copies rotated so that the working set exceeds the Infinity Cache.
+the weight copies rotated so that the working set exceeds the Infinity Cache;
+the launches are replayed from a HIP graph, as a serving loop would issue them.
 `cpu_baseline` is the NumPy oracle timed on a bounded sample of the same
 workload on this host's cores.
+
+`--calibrate-copy` runs nothing but a plain device copy of a known size; it
+exists so that the FETCH_SIZE / WRITE_SIZE counters of a profiler run of this
+script can be scaled to bytes.
 """
 from __future__ import annotations
 
@@ -35,6 +40,12 @@ from paper_2603_08185_amd import binding as serq  # noqa: E402
 
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, 5.0 POP/s
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, 8 TB/s
+
+# HBM traffic of one serq_linear launch of the benchmark workload, from two counter runs
+# (FETCH_SIZE, then WRITE_SIZE) of this script scaled by the same counters of --calibrate-copy;
+# the runs and the arithmetic are in profiles/serq_mfma_kernel_cfg3_up_M4096_hbm_traffic.md.
+# None until measured for the kernel as it stands.
+LINEAR_TRAFFIC_BYTES = None
 
 
 def _events(n):
@@ -92,7 +103,7 @@ def decode_bytes(spec) -> float:
     return N * K / 2 + 2.0 * r * N + 4 * N + M * K * spec.abits / 8 + 4 * M + M * N * out_b
 
 
-def bench_decode(L, pk, iters: int = 200):
+def bench_decode(L, pk, reps: int = 5):
     """M = 1 on the same layer; weights + R rotated over > 512 MB of distinct copies."""
     dev = "cuda:0"
     spec = workloads.config3("up", 1)
@@ -107,25 +118,43 @@ def bench_decode(L, pk, iters: int = 200):
     Rps = [Rp0.clone() for _ in range(ncopy)]
     ws = serq.workspace(M, N, K, spec.r, spec.abits, dev)
     Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    n = 4 * ncopy
 
-    def run(rotate: bool, n: int):
-        e0, e1 = _events(2)
-        torch.cuda.synchronize()
-        e0.record()
+    def launches(rotate: bool):
         for i in range(n):
             j = i % ncopy if rotate else 0
             serq.linear(Xq, scale, spec.abits, Wqs[j], pk.wscale, M, N, K, Rp=Rps[j], r=spec.r, Y=Y, ws=ws)
+
+    def timed(fn):
+        e0, e1 = _events(2)
+        torch.cuda.synchronize()
+        e0.record()
+        fn()
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
 
-    run(True, 2 * ncopy)
-    cold = min(run(True, iters) for _ in range(3))
-    warm = min(run(False, iters) for _ in range(3))
+    launches(True)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()          # graph capture needs a non-default stream (default priority)
+    graphs = {}
+    for rotate in (True, False):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                launches(rotate)
+        graphs[rotate] = g
+    torch.cuda.synchronize()
+    for g in graphs.values():
+        g.replay()
+    cold = min(timed(graphs[True].replay) for _ in range(reps))
+    warm = min(timed(graphs[False].replay) for _ in range(reps))
+    cold_stream = min(timed(lambda: launches(True)) for _ in range(reps))
     b = decode_bytes(spec)
     return {"workload": spec.name, "bytes": b, "copies": ncopy,
             "us_hbm": cold * 1e3, "gbs_hbm": b / (cold * 1e-3) / 1e9,
             "us_cache_warm": warm * 1e3, "gbs_cache_warm": b / (warm * 1e-3) / 1e9,
+            "us_hbm_stream_launch": cold_stream * 1e3,
             "frac_hbm_peak": b / (cold * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
 
@@ -149,6 +178,15 @@ def cpu_baseline(L, n_tokens: int = 192):
                       f"{dt:.2f} s", "host_cpus": len(os.sched_getaffinity(0))}, Y
 
 
+def calibrate_copy(nbytes: int = 1 << 30, reps: int = 3):
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").fill_(1)
+    dst = torch.empty_like(src)
+    for _ in range(reps):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"calibrate_copy_bytes": nbytes, "launches": reps}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -156,6 +194,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the M=1 decode leg")
+    ap.add_argument("--calibrate-copy", action="store_true", help="only run a plain 1 GiB device copy (counter calibration)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -164,6 +203,9 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     serq.lib()
+    if a.calibrate_copy:
+        calibrate_copy()
+        return
 
     pre = bench_prefill(a.steps, a.warmup)
     spec = pre["spec"]
@@ -180,7 +222,7 @@ def main():
                    "M": spec.M, "K": spec.K, "N": spec.N, "r": spec.r, "abits": spec.abits},
         "roofline": {"bound": "mfma", "kernel": "serq_mfma_kernel<8> (serq_linear)",
                      "achieved": round(pre["tops_linear"], 2), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": round(pre["tops_linear"] / INT8_PEAK_TOPS, 4), "traffic": None,
+                     "frac": round(pre["tops_linear"] / INT8_PEAK_TOPS, 4), "traffic": LINEAR_TRAFFIC_BYTES,
                      "kernel_ms": round(pre["linear_ms"], 5)},
         "quantize_act": {"ms": round(pre["quant_ms"], 5), "gbs": round(pre["quant_gbs"], 1),
                          "frac_hbm_peak": round(pre["quant_gbs"] / HBM_PEAK_GBS, 4)},
