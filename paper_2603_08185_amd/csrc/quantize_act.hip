@@ -4,9 +4,14 @@
 //   scale[m] = max_k |x~| / qmax,  code = clip(rne(x~ / scale), -qmax, qmax).
 // One 256-thread workgroup per token; the row is read from HBM once, in
 // 16-byte pieces, and kept in registers between the absmax pass and the
-// quantise pass.  All arithmetic that decides a code is IEEE fp32 (one
-// multiply, one division, one round-to-nearest-even), so the codes do not
-// depend on how the reduction is scheduled.
+// quantise pass.  (Variants that walk several tokens per workgroup or per wave,
+// with the next row prefetched and the flattening factors kept in registers,
+// measured slower: thousands of small independent workgroups overlap their
+// phases better than any hand-made pipeline here.)  Every code equals what IEEE
+// fp32 arithmetic gives for one multiply, one division and one
+// round-to-nearest-even (codes8 below avoids most of the divisions without
+// changing any result), so the codes do not depend on how the reduction is
+// scheduled.
 #include "serq_device.h"
 
 namespace serq {
@@ -52,26 +57,54 @@ __device__ __forceinline__ float absmax8(const float v[8], float m) {
   return m;
 }
 
+// Codes of 8 flattened values, bit-identical to clip(rne(v / sc)) in IEEE fp32, at the price of
+// a multiplication per value.  t = v * rcp(sc) is within 2^-22 |t| of the correctly rounded
+// quotient (one ulp from the reciprocal, half an ulp from the product, half an ulp from the
+// quotient's own rounding), so the two round to the same integer unless t lies within that distance
+// of a half-integer; only then (the ties of synthetic inputs, and about one piece in a hundred
+// otherwise) are the divisions carried out.  The margin used is 2^-20 max(|t|, 1) over the piece.
+// Clamping before rounding equals rounding before clamping for integer bounds, and adding
+// 1.5 * 2^23 rounds to nearest-even and leaves the two's-complement code in the low mantissa bits.
 template <int ABITS>
-__device__ __forceinline__ void quant_store8(const float v[8], float sc, void* xq_row, int chunk) {
+__device__ __forceinline__ void codes8(const float v[8], float sc, float rsc, uint32_t u[8]) {
   constexpr float q = (float)((1 << (ABITS - 1)) - 1);
-  int c[8];
+  constexpr float kMagic = 12582912.0f;
+  float maxd = 0.0f, maxt = 1.0f;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    float t = rintf(v[i] / sc);            // IEEE division, then round-half-to-even
-    t = fminf(fmaxf(t, -q), q);
-    c[i] = (int)t;
+    const float tc = __builtin_amdgcn_fmed3f(v[i] * rsc, -q, q);
+    const float uf = tc + kMagic;
+    u[i] = __float_as_uint(uf);
+    maxd = fmaxf(maxd, fabsf(tc - (uf - kMagic)));
+    maxt = fmaxf(maxt, fabsf(tc));
   }
+  if (0.5f - maxd < 9.5367431640625e-07f * maxt) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float t = rintf(v[i] / sc);          // IEEE division, then round-half-to-even
+      t = fminf(fmaxf(t, -q), q);
+      u[i] = __float_as_uint(t + kMagic);
+    }
+  }
+}
+
+template <int ABITS>
+__device__ __forceinline__ void quant_store8(const float v[8], float sc, void* xq_row, int chunk) {
+  const float rsc = __builtin_amdgcn_rcpf(sc);
+  uint32_t u[8];
+  codes8<ABITS>(v, sc, rsc, u);
   if constexpr (ABITS == 8) {
-    uint32_t d0 = (c[0] & 0xff) | ((c[1] & 0xff) << 8) | ((c[2] & 0xff) << 16) | ((uint32_t)(c[3] & 0xff) << 24);
-    uint32_t d1 = (c[4] & 0xff) | ((c[5] & 0xff) << 8) | ((c[6] & 0xff) << 16) | ((uint32_t)(c[7] & 0xff) << 24);
+    // low bytes of u[0..3] and u[4..7]
+    const uint32_t d0 = __builtin_amdgcn_perm(u[1], u[0], 0x0c0c0400u) | __builtin_amdgcn_perm(u[3], u[2], 0x04000c0cu);
+    const uint32_t d1 = __builtin_amdgcn_perm(u[5], u[4], 0x0c0c0400u) | __builtin_amdgcn_perm(u[7], u[6], 0x04000c0cu);
     ((uint2*)xq_row)[chunk] = make_uint2(d0, d1);
   } else {
-    uint32_t d = 0;
+    // byte j = code j in the low nibble, code 4+j in the high nibble
+    uint32_t w[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      d |= ((uint32_t)(c[j] & 0xf) | ((uint32_t)(c[4 + j] & 0xf) << 4)) << (8 * j);
-    ((uint32_t*)xq_row)[chunk] = d;
+    for (int j = 0; j < 4; ++j) w[j] = (u[4 + j] << 4) | (u[j] & 0xfu);
+    ((uint32_t*)xq_row)[chunk] =
+        __builtin_amdgcn_perm(w[1], w[0], 0x0c0c0400u) | __builtin_amdgcn_perm(w[3], w[2], 0x04000c0cu);
   }
 }
 
