@@ -158,9 +158,6 @@ struct LinearArgs {
   int32_t* acc_out; int64_t ldacc;      // non-NULL: store raw accumulators instead of Y
   void* workspace; size_t workspace_bytes;
   int splitk; int groupm; int coltiles; int skinny_waves;
-#ifdef SERQ_SKINNY_DBG
-  void* dbg;
-#endif
 };
 
 int skinny_splitk_auto(int M, int N, int K);

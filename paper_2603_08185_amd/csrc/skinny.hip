@@ -6,28 +6,42 @@
 //
 // Work decomposition: a workgroup of 4 or 8 waves owns one block of 32 output
 // channels and one slice of K (the host splits K only when N alone gives too
-// few workgroups to fill the chip).  The 1-KiB weight fragments of the block
-// are contiguous in memory; wave w of W takes fragments w, w+W, ... of the slice,
-// four at a time: one coalesced 16-byte load per lane and fragment, all four in
-// flight before the first is used.  The nibbles are widened to int8 (x16) in
-// registers and fed to two 32x32x32 int8 MFMAs per fragment whose B operand is
-// the token block (rows >= M are zero) -- the matrix unit is nearly idle, the
-// point is that it costs no VALU work to reduce over K.  The rank-r term runs
-// through 32x32x16 f16/bf16 MFMAs on the packed R fragments (one fragment per
-// wave) into a second, fp32 accumulator.
+// few workgroups).  The 1-KiB weight fragments of the block are contiguous in
+// memory; wave w of W takes the groups w, w+W, ... of four or eight consecutive
+// fragments: one coalesced 16-byte load per lane and fragment, the whole group
+// in flight before its first fragment is used.
 //
-// The waves are combined through LDS in a fixed order.  With a split K the
-// workgroup stores its partial sums (INT32 for the main term, fp32 for the
-// low-rank term, which only slice 0 computes) to the workspace and a second,
-// small kernel adds the slices in a fixed order and applies the epilogue -- the
-// kernel boundary is the only synchronisation, so no device-wide fences or
-// atomics are needed and results are run-to-run identical.
+// The token operand of a group (M rows of 4*64 or 8*64 channels) is what limits
+// a naive version: read per lane in MFMA operand order it touches 32 cache
+// lines per load instruction and the CU's L1 spends more cycles on it than on
+// the weights.  Here a wave fetches it with whole-line direct-to-LDS loads
+// (8, 4 or 2 rows of 128/256/512 contiguous bytes per instruction, no staging
+// registers) into a wave-private LDS region -- piece order xor-swizzled per
+// row, so the per-token operand reads are bank-conflict free -- and reads the
+// operands back from there.  Loads retire in order, so the token loads are
+// issued before the weight loads of the group (cache hits must not queue behind
+// the HBM stream) and one hand-counted wait on "all but the weight loads"
+// covers them.  No barrier is needed in the main loop.
+//
+// The nibbles are widened to int8 (x16) in registers and fed to two 32x32x32
+// int8 MFMAs per fragment whose B operand is the token block (rows >= M are
+// zero) -- the matrix unit is nearly idle, the point is that it costs no VALU
+// work to reduce over K.  The rank-r term runs through 32x32x16 f16/bf16 MFMAs
+// on the packed R fragments (one fragment per wave) into a second, fp32
+// accumulator.
+//
+// The waves are combined through LDS in a fixed order (each wave parks its
+// partial sums in its own region: one barrier in the whole kernel).  With a
+// split K the workgroup stores its partial sums (INT32 for the main term, fp32
+// for the low-rank term, which only slice 0 computes) to the workspace and a
+// second, small kernel adds the slices in a fixed order and applies the
+// epilogue -- the kernel boundary is the only synchronisation, so no
+// device-wide fences or atomics are needed and results are run-to-run
+// identical.
 #include "serq_device.h"
 
 namespace serq {
 namespace {
-
-
 
 struct SkinnyParams {
   const uint8_t* Xq; const float* scale;
@@ -37,10 +51,8 @@ struct SkinnyParams {
   void* Y; int y_dtype; int64_t ldy;
   int32_t* acc_out; int64_t ldacc;
   int splitk;
+  int region;                           // bytes of LDS per wave
   int32_t* part_i; float* part_f;       // [N/32][splitk][1024] each
-#ifdef SERQ_SKINNY_DBG
-  unsigned long long* dbg;
-#endif
 };
 
 // y for (token m, channel n) from the two sums; one store
@@ -57,15 +69,36 @@ __device__ __forceinline__ void finish(const SkinnyParams& p, int m, int n, int 
   else ((uint16_t*)p.Y)[o] = f32_to_f16_rne(y);
 }
 
-template <int ABITS, int kWaves, int kUnroll>
-__global__ __launch_bounds__(kWaves * 64) void serq_skinny_kernel(const SkinnyParams p) {
-  constexpr int kThreads = kWaves * 64;
-  constexpr int kPitch = 65;                            // words per accumulator register row: an odd pitch spreads the gather over the banks
-  __shared__ int red[kWaves][16 * kPitch];              // used for the INT32, then the fp32 partials
 
-#ifdef SERQ_SKINNY_DBG
-  const unsigned long long dbg_t0 = wall_clock64();
-#endif
+__device__ __forceinline__ uint32_t lds_addr(const void* ptr) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)ptr;
+}
+// 16 bytes per lane, no staging registers: global (sbase + voff) -> LDS (lds_base_uniform + 16 * lane)
+__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base_uniform) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_base_uniform), "v"(voff), "s"(sbase) : "memory", "m0");
+}
+
+// Geometry of the token staging for one group of kGroup consecutive fragments (4 or 8).
+template <int ABITS, int kGroup>
+struct Stage {
+  static constexpr int FB = 8 * ABITS;                  // bytes of one token's 64 channels
+  static constexpr int P = kGroup * FB / 16;            // 16-byte pieces per token row: 8, 16 or 32
+  static constexpr int RPI = 64 / P;                    // token rows one load instruction covers: 8, 4 or 2
+  static constexpr int NI = 32 / RPI < 8 ? 32 / RPI : 8; // load instructions the kernel provides for: at most 8 KiB of token rows per group
+  static constexpr int ROWB = P * 16;                   // 128, 256 or 512 bytes
+  // xor applied to the piece index of row m: spreads 16 consecutive rows over the 16 bank groups
+  // (rows of 128 bytes already alternate between two halves of the banks)
+  static __device__ __forceinline__ int sw(int m) { return P >= 16 ? (m & 15) : ((m >> 1) & 7); }
+};
+
+template <int ABITS, int kWaves, int kGroup>
+__global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGroup == 8 ? 4 : 5, 8))) void serq_skinny_kernel(const SkinnyParams p) {
+  constexpr int kThreads = kWaves * 64;
+  constexpr int SH = (ABITS == 8) ? 4 : 8;
+  typedef Stage<ABITS, kGroup> S;
+  extern __shared__ __align__(16) uint8_t lds[];        // per wave: token staging, then the partial sums
+
   const int tid = threadIdx.x;
   const int w = tid >> 6, l = tid & 63;
   const int m = l & 31, g = l >> 5;
@@ -74,54 +107,38 @@ __global__ __launch_bounds__(kWaves * 64) void serq_skinny_kernel(const SkinnyPa
   const int KB = p.K >> 6;
   const int kb0 = (int)(((int64_t)KB * ks) / p.splitk);
   const int kb1 = (int)(((int64_t)KB * (ks + 1)) / p.splitk);
-  constexpr int SH = (ABITS == 8) ? 4 : 8;
   const size_t rowbytes = (size_t)p.K * ABITS / 8;
 
   const bool mv = m < p.M;
   const uint8_t* xrow = p.Xq + (size_t)(mv ? m : 0) * rowbytes;
   const u4* wfr = p.Wq + (size_t)nb * KB * 64 + l;
+  uint8_t* my = lds + (size_t)w * p.region;
 
   v16i acc;
-  v16f accf;
 #pragma unroll
-  for (int e = 0; e < 16; ++e) { acc[e] = 0; accf[e] = 0.0f; }
+  for (int e = 0; e < 16; ++e) acc[e] = 0;
 
-  // Everything this wave will need is requested before anything is used, so that the
-  // workgroup pays the memory latency once: the operands of the rank-r term (blocks of
-  // 16 salient channels, slice 0 only; up to kLrMax blocks per wave are prefetched) ...
+  // ---- cache-resident operands of the epilogue, requested first ---------------
+  // the token codes of the rank-r term (blocks of 16 salient channels, slice 0 only; one block per wave
+  // is requested up front) ...
   const bool has_lr = p.r > 0 && p.acc_out == nullptr;
   const bool lr_here = has_lr && ks == 0;
   const int JB = p.r >> 4;
   const bool bf = p.r_dtype == SERQ_BF16;
-  constexpr int kLrMax = 2;
-  u4 rf[kLrMax];
-  u2 xc[kLrMax];
   const u4* rfr = p.Rp + (size_t)nb * JB * 64 + l;
-  auto lr_load = [&](int jb, u4& r_out, u2& x_out) {
-    r_out = __builtin_nontemporal_load(&rfr[(size_t)jb * 64]);
+  auto lr_load_x = [&](int jb) {
+    u2 x = {0u, 0u};
     const int col = p.s_begin + jb * 16 + g * 8;        // first of this lane's 8 channels
-    if constexpr (ABITS == 8) x_out = *(const u2*)(xrow + col);
-    else { x_out.x = *(const uint32_t*)(xrow + (col >> 1)); x_out.y = 0; }
+    if (mv) {
+      if constexpr (ABITS == 8) x = *(const u2*)(xrow + col);
+      else x.x = *(const uint32_t*)(xrow + (col >> 1));
+    }
+    return x;
   };
-  auto lr_mfma = [&](const u4& r_in, const u2& x_in) {
-    int c[8];
-    if constexpr (ABITS == 8) codes_from_a8(x_in.x, x_in.y, c);
-    else codes_from_a4(x_in.x, c);
-    u4 xf = codes8_to_16bit(c, bf);
-    if (!mv) xf = u4{0u, 0u, 0u, 0u};
-    if (bf)
-      accf = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, r_in), __builtin_bit_cast(v8bf, xf),
-                                                     accf, 0, 0, 0);
-    else
-      accf = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, r_in), __builtin_bit_cast(v8h, xf),
-                                                    accf, 0, 0, 0);
-  };
-  if (lr_here) {
-#pragma unroll
-    for (int q = 0; q < kLrMax; ++q)
-      if (w + q * kWaves < JB) lr_load(w + q * kWaves, rf[q], xc[q]);
-  }
-  // ... the scales of the outputs this thread will finish ...
+  const bool lr_first = lr_here && w < JB;
+  u2 xc = {0u, 0u};
+  if (lr_first) xc = lr_load_x(w);
+  // ... and the scales of the outputs this thread will finish
   constexpr int NQ = 1024 / kThreads;
   float sc_m[NQ], sc_n[NQ];
 #pragma unroll
@@ -133,126 +150,123 @@ __global__ __launch_bounds__(kWaves * 64) void serq_skinny_kernel(const SkinnyPa
       sc_n[q] = p.wscale[nb * 32 + (id & 31)];
     }
   }
+  u4 rf = {0u, 0u, 0u, 0u};
+  if (lr_first) rf = __builtin_nontemporal_load(&rfr[(size_t)w * 64]);
 
-  // ... and the main integer contraction over this workgroup's K slice, in batches of kUnroll
-  // fragments per wave.  Registers are kept few on purpose: many resident waves hide the latency.
-  struct Batch { u4 wp[kUnroll]; u4 x0[kUnroll]; u4 x1[ABITS == 8 ? kUnroll : 1]; };
-  auto load_batch = [&](int kb, Batch& B) {
+  // ---- the integer contraction over this workgroup's K slice ------------------
+  // staging role of this lane: row srow0 + RPI*j of instruction j, slot l % P of the row
+  const int srow0 = l / S::P, slot = l % S::P;
+  const int nfr = kb1 - kb0;                            // fragments in the slice
+  const uint8_t* xslice = p.Xq + (size_t)kb0 * S::FB;
+  const uint32_t my_lds = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_addr(my));
+#pragma unroll 1
+  for (int gi = w; gi * kGroup < nfr; gi += kWaves) {
+    const int f0 = gi * kGroup;                         // first fragment of the group, relative to the slice
+    // token rows of the group straight into LDS, whole lines, ahead of the weight loads
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int kbu = kb + u * kWaves;
-      const bool ok = kbu < kb1;
-      const int kc = ok ? kbu : kb0;                    // always a valid fragment
-      B.wp[u] = __builtin_nontemporal_load(&wfr[(size_t)kc * 64]);   // streamed once: do not keep it in the caches
-      if (!ok) B.wp[u] = u4{0u, 0u, 0u, 0u};            // zero weights contribute nothing
-      if constexpr (ABITS == 8) {
-        const u4* xp = (const u4*)(xrow + (size_t)kc * 64 + g * 32);
-        B.x0[u] = xp[0];
-        B.x1[u] = xp[1];
-      } else {
-        B.x0[u] = *(const u4*)(xrow + (size_t)kc * 32 + g * 16);
+    for (int j = 0; j < S::NI; ++j) {
+      if (S::RPI * j < p.M) {                           // uniform
+        const int row = srow0 + S::RPI * j;
+        const int rowc = row < p.M ? row : p.M - 1;     // rows past M: any valid address, never read back
+        int col = f0 * S::FB + ((slot ^ S::sw(row)) << 4);
+        col = col < nfr * S::FB ? col : 0;              // pieces past a ragged slice likewise
+        dma16(xslice, (uint32_t)rowc * (uint32_t)rowbytes + (uint32_t)col, my_lds + 1024u * j);
       }
     }
-  };
-  auto mul_batch = [&](const Batch& B) {
+    u4 wp[kGroup];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
+    for (int u = 0; u < kGroup; ++u) {
+      const bool ok = f0 + u < nfr;
+      wp[u] = __builtin_nontemporal_load(&wfr[(size_t)(kb0 + (ok ? f0 + u : 0)) * 64]);   // streamed once: do not keep it in the caches
+      if (!ok) wp[u] = u4{0u, 0u, 0u, 0u};              // zero weights contribute nothing
+    }
+    // the kGroup weight loads are the only vector-memory operations younger than the token rows
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(kGroup) : "memory");
+#pragma unroll
+    for (int u = 0; u < kGroup; ++u) {
+      if (f0 + u >= kb1 - kb0) break;                   // uniform over the wave
       v4i a0, a1, b0, b1;
-      unpack_frag(B.wp[u], a0, a1);
-      if constexpr (ABITS == 8) {
-        b0 = as_v4i(B.x0[u]);
-        b1 = as_v4i(B.x1[u]);
-      } else {
-        unpack_frag(B.x0[u], b0, b1);
+      unpack_frag(wp[u], a0, a1);
+      b0 = (v4i){0, 0, 0, 0};
+      b1 = (v4i){0, 0, 0, 0};
+      if (mv) {
+        const uint8_t* xr = my + m * S::ROWB;
+        if constexpr (ABITS == 8) {
+          b0 = *(const v4i*)(xr + (((4 * u + 2 * g) ^ S::sw(m)) << 4));
+          b1 = *(const v4i*)(xr + (((4 * u + 2 * g + 1) ^ S::sw(m)) << 4));
+        } else {
+          unpack_frag(*(const u4*)(xr + (((2 * u + g) ^ S::sw(m)) << 4)), b0, b1);
+        }
       }
-      if (!mv) { b0 = (v4i){0, 0, 0, 0}; b1 = (v4i){0, 0, 0, 0}; }
       acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, acc, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, acc, 0, 0, 0);
     }
-  };
-  for (int kb = kb0 + w; kb < kb1; kb += kWaves * kUnroll) {
-    Batch B;
-    load_batch(kb, B);
-    __builtin_amdgcn_sched_barrier(0);                  // every load of the batch is in flight before the first use
-    mul_batch(B);
   }
 
-  if (lr_here) {
+  // ---- the rank-r term ----------------------------------------------------------
+  v16f accf;
 #pragma unroll
-    for (int q = 0; q < kLrMax; ++q)
-      if (w + q * kWaves < JB) lr_mfma(rf[q], xc[q]);
-    for (int jb = w + kLrMax * kWaves; jb < JB; jb += kWaves) {   // ranks beyond the prefetched blocks
-      u4 r1; u2 x1;
-      lr_load(jb, r1, x1);
-      lr_mfma(r1, x1);
+  for (int e = 0; e < 16; ++e) accf[e] = 0.0f;
+  auto lr_mfma = [&](const u4& r_in, const u2& x_in) {
+    int c[8];
+    if constexpr (ABITS == 8) codes_from_a8(x_in.x, x_in.y, c);
+    else codes_from_a4(x_in.x, c);
+    u4 xf = codes8_to_16bit(c, bf);                     // zero codes for lanes without a token
+    if (bf)
+      accf = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, r_in), __builtin_bit_cast(v8bf, xf),
+                                                     accf, 0, 0, 0);
+    else
+      accf = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, r_in), __builtin_bit_cast(v8h, xf),
+                                                    accf, 0, 0, 0);
+  };
+  if (lr_first) lr_mfma(rf, xc);
+  if (lr_here) {
+    for (int jb = w + kWaves; jb < JB; jb += kWaves) {  // ranks beyond the first block of each wave
+      const u4 r1 = __builtin_nontemporal_load(&rfr[(size_t)jb * 64]);
+      lr_mfma(r1, lr_load_x(jb));
     }
   }
 
-#ifdef SERQ_SKINNY_DBG
-  const unsigned long long dbg_t1 = wall_clock64();
-#endif
   // ---- combine the waves ----------------------------------------------------
   // accumulator register e of lane l holds channel 8*(e/4) + 4*(l/32) + e%4 of
-  // the block and token l%32; only tokens < M are exchanged.
+  // the block and token l%32; only tokens < M are exchanged.  A wave parks its
+  // partials in its own region (dead as token staging by now): register e, lane
+  // half h, token t at word (2e + h) * Mp + t, the fp32 partials 32*Mp words
+  // further; the odd pitch Mp spreads the gather over the banks.
   // Thread tid finishes (token q/32, channel q%32) for q = tid, tid + kThreads, ...
+  const int Mp = p.M | 1;
   const int nwl = JB < kWaves ? JB : kWaves;              // waves that hold low-rank sums
   if (mv) {
+    int* red = reinterpret_cast<int*>(my);
 #pragma unroll
-    for (int e = 0; e < 16; ++e) red[w][e * kPitch + l] = acc[e];
+    for (int e = 0; e < 16; ++e) red[(2 * e + g) * Mp + m] = acc[e];
+    if (lr_here && w < nwl) {
+      float* redf = reinterpret_cast<float*>(my) + 32 * Mp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) redf[(2 * e + g) * Mp + m] = accf[e];
+    }
   }
   __syncthreads();
-  int tot_i[NQ];
-  float tot_f[NQ];
-#pragma unroll
-  for (int q = 0; q < NQ; ++q) {
-    const int id = tid + q * kThreads;
-    const int nl = id & 31, mt = id >> 5;
-    const int e_src = 4 * (nl >> 3) + (nl & 3);
-    const int l_src = mt + 32 * ((nl >> 2) & 1);
-    tot_i[q] = 0;
-    tot_f[q] = 0.0f;
-    if (mt < p.M) {
-#pragma unroll
-      for (int ww = 0; ww < kWaves; ++ww) tot_i[q] += red[ww][e_src * kPitch + l_src];
-    }
-  }
-  if (has_lr) {                                           // uniform over the grid
-    __syncthreads();
-    float* redf = reinterpret_cast<float*>(&red[0][0]);
-    if (mv && w < nwl && lr_here) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) redf[w * 16 * kPitch + e * kPitch + l] = accf[e];
-    }
-    __syncthreads();
-    if (lr_here) {
-#pragma unroll
-      for (int q = 0; q < NQ; ++q) {
-        const int id = tid + q * kThreads;
-        const int nl = id & 31, mt = id >> 5;
-        const int e_src = 4 * (nl >> 3) + (nl & 3);
-        const int l_src = mt + 32 * ((nl >> 2) & 1);
-        if (mt < p.M)
-          for (int ww = 0; ww < nwl; ++ww) tot_f[q] += redf[ww * 16 * kPitch + e_src * kPitch + l_src];
-      }
-    }
-  }
-
 #pragma unroll
   for (int q = 0; q < NQ; ++q) {
     const int id = tid + q * kThreads;
     const int nl = id & 31, mt = id >> 5;
     if (mt >= p.M) continue;
+    const int src = (2 * (4 * (nl >> 3) + (nl & 3)) + ((nl >> 2) & 1)) * Mp + mt;
+    int tot_i = 0;
+    float tot_f = 0.0f;
+#pragma unroll
+    for (int ww = 0; ww < kWaves; ++ww) tot_i += *reinterpret_cast<const int*>(lds + (size_t)ww * p.region + 4 * src);
+    if (lr_here)
+      for (int ww = 0; ww < nwl; ++ww) tot_f += *reinterpret_cast<const float*>(lds + (size_t)ww * p.region + 4 * (32 * Mp + src));
     if (p.splitk > 1) {
       // partial sums of this slice; the reduce kernel finishes the job
-      p.part_i[((size_t)nb * p.splitk + ks) * 1024 + id] = tot_i[q];
-      if (lr_here) p.part_f[(size_t)nb * 1024 + id] = tot_f[q];
+      p.part_i[((size_t)nb * p.splitk + ks) * 1024 + id] = tot_i;
+      if (lr_here) p.part_f[(size_t)nb * 1024 + id] = tot_f;
     } else {
-      finish(p, mt, nb * 32 + nl, tot_i[q] >> SH, tot_f[q], sc_m[q], sc_n[q]);   // exact shift: the sum is a multiple of 2^SH
+      finish(p, mt, nb * 32 + nl, tot_i >> SH, tot_f, sc_m[q], sc_n[q]);   // exact shift: the sum is a multiple of 2^SH
     }
   }
-#ifdef SERQ_SKINNY_DBG
-  if (p.dbg && tid == 0) { p.dbg[blockIdx.x * 3] = dbg_t0; p.dbg[blockIdx.x * 3 + 1] = dbg_t1; p.dbg[blockIdx.x * 3 + 2] = wall_clock64(); }
-#endif
 }
 
 // second kernel of a split-K launch: one workgroup per block of 32 channels
@@ -278,8 +292,8 @@ int skinny_splitk_auto(int M, int N, int K) {
   (void)M;
   const int nblk = N / 32;
   const int KB = K / 64;
-  int s = (256 + nblk - 1) / nblk;           // aim for one workgroup per compute unit; splitting further only adds passes
-  const int smax = KB / 16 > 0 ? KB / 16 : 1;          // keep >= 2 fragments per wave of an 8-wave workgroup
+  int s = (128 + nblk - 1) / nblk;           // 128 sixteen-wave workgroups already keep the memory system busy; a split costs a second launch
+  const int smax = KB / 16 > 0 ? KB / 16 : 1;          // keep >= 16 fragments per slice
   if (s > smax) s = smax;
   if (s > 16) s = 16;
   if (s < 1) s = 1;
@@ -299,9 +313,6 @@ int launch_skinny(const LinearArgs& a, hipStream_t st) {
   p.M = a.M; p.N = a.N; p.K = a.K;
   p.Y = a.Y; p.y_dtype = a.y_dtype; p.ldy = a.ldy;
   p.acc_out = a.acc_out; p.ldacc = a.ldacc;
-#ifdef SERQ_SKINNY_DBG
-  p.dbg = (unsigned long long*)a.dbg;
-#endif
   int splitk = a.splitk > 0 ? a.splitk : skinny_splitk_auto(a.M, a.N, a.K);
   const int KB = a.K / 64;
   if (splitk > KB) splitk = KB;
@@ -315,16 +326,40 @@ int launch_skinny(const LinearArgs& a, hipStream_t st) {
   p.splitk = splitk;
   p.part_i = splitk > 1 ? (int32_t*)a.workspace : nullptr;
   p.part_f = splitk > 1 ? (float*)((char*)a.workspace + nblk * (size_t)splitk * 1024 * 4) : nullptr;
-  // waves per workgroup: 8 when the slice is long enough to give each of them several batches,
-  // else 4 -- launching and combining waves costs more than it hides on a short slice
+
+  // Waves per workgroup: 8 once the slice gives each of them a group of fragments, else 4.  (16-wave
+  // workgroups measured slower: their registers and LDS allow one workgroup per CU where two or three
+  // smaller ones overlap each other's start-up and epilogue.)
+  const int KBs = (KB + splitk - 1) / splitk;           // longest slice, in fragments
   int nw = a.skinny_waves;
-  if (nw != 4 && nw != 8) nw = (KB / splitk >= 128) ? 8 : 4;
+  if (nw != 4 && nw != 8) nw = KBs >= 32 ? 8 : 4;
+  // Fragments per group: 8 when every wave gets a full group of 8 and the token rows of such a group
+  // stay within 8 KiB of LDS per wave, else 4.
+  const int rowb8 = 8 * 8 * a.abits / 16 * 16;          // bytes of a token row of a group of 8
+  const int rpi8 = 1024 / rowb8;
+  const bool can8 = (a.M + rpi8 - 1) / rpi8 * rpi8 * rowb8 <= 8192;
+  const int grp = (KBs >= 8 * nw && can8) ? 8 : 4;
+  // LDS per wave: the token rows of one group, later the wave's partial sums
+  const int rowb = grp * 8 * a.abits / 16 * 16;
+  const int rpi = 1024 / rowb;
+  const int rows = (a.M + rpi - 1) / rpi * rpi;
+  const bool has_lr = p.r > 0 && p.acc_out == nullptr;
+  const int Mp = a.M | 1;
+  int region = rows * rowb;
+  const int red = (has_lr ? 2 : 1) * 32 * Mp * 4;
+  if (red > region) region = red;
+  region = (region + 15) & ~15;
+  p.region = region;
+  const size_t lds_bytes = (size_t)region * nw;
+
   dim3 grid((unsigned)(nblk * splitk)), block((unsigned)nw * 64);
-#define SERQ_SKINNY_LAUNCH(AB, NW) hipLaunchKernelGGL((serq_skinny_kernel<AB, NW, 4>), grid, block, 0, st, p)
+#define SERQ_SKINNY_LAUNCH(AB, NW, G) hipLaunchKernelGGL((serq_skinny_kernel<AB, NW, G>), grid, block, lds_bytes, st, p)
   if (a.abits == 8) {
-    if (nw == 4) SERQ_SKINNY_LAUNCH(8, 4); else SERQ_SKINNY_LAUNCH(8, 8);
+    if (nw == 4) { if (grp == 4) SERQ_SKINNY_LAUNCH(8, 4, 4); else SERQ_SKINNY_LAUNCH(8, 4, 8); }
+    else { if (grp == 4) SERQ_SKINNY_LAUNCH(8, 8, 4); else SERQ_SKINNY_LAUNCH(8, 8, 8); }
   } else {
-    if (nw == 4) SERQ_SKINNY_LAUNCH(4, 4); else SERQ_SKINNY_LAUNCH(4, 8);
+    if (nw == 4) { if (grp == 4) SERQ_SKINNY_LAUNCH(4, 4, 4); else SERQ_SKINNY_LAUNCH(4, 4, 8); }
+    else { if (grp == 4) SERQ_SKINNY_LAUNCH(4, 8, 4); else SERQ_SKINNY_LAUNCH(4, 8, 8); }
   }
 #undef SERQ_SKINNY_LAUNCH
   if (hipGetLastError() != hipSuccess) return SERQ_EHIP;

@@ -166,6 +166,36 @@ def test_gemm_i32_skinny(abits, M, N, K, splitk):
     assert torch.equal(got, again)
 
 
+# Decode kernel variants: 4/8/16 waves per workgroup; token slice staged in LDS (small M*K) or read per
+# lane (large M*K); slices longer than one batch of fragments per wave (K = 13312 with 16 waves).
+@pytest.mark.parametrize("abits", [4, 8])
+@pytest.mark.parametrize("waves", [4, 8, 16])
+@pytest.mark.parametrize("M,N,K", [(1, 64, 4096), (4, 64, 13312), (16, 96, 4096), (32, 64, 2048), (32, 64, 8192),
+                                   (7, 32, 832), (2, 32, 64)])
+def test_gemm_i32_skinny_wave_counts(abits, waves, M, N, K):
+    Xq, Wq = _codes(M, K, N, abits, seed=M + N + K + waves)
+    pk, xq, _ = _device_codes(Xq, Wq, abits)
+    want = orc.gemm_i32(Xq, Wq)
+    ws = serq.workspace(M, N, K, 0, abits, DEV)
+    for splitk in (1, 2):
+        if splitk > K // 64:
+            continue
+        fl = serq.flags(serq.PATH_SKINNY, splitk=splitk, groupm=waves // 4)
+        got = serq.gemm_i32(xq, abits, pk.Wq, M, N, K, ws=ws, flags_=fl)
+        assert np.array_equal(got.cpu().numpy(), want), f"splitk={splitk}"
+
+
+@pytest.mark.parametrize("abits", [4, 8])
+@pytest.mark.parametrize("waves", [4, 8, 16])
+@pytest.mark.parametrize("M,K,N,r", [(1, 4096, 64, 128), (16, 2048, 96, 256), (32, 2048, 64, 128), (32, 8192, 64, 32),
+                                     (3, 832, 32, 16)])
+def test_layer_skinny_wave_counts(abits, waves, M, K, N, r):
+    # rank-r partials beside (small M) and on top of (M = 32, 16 waves) the integer partials in LDS
+    spec = _small_spec(abits, M, K, N, r)
+    _run_layer(spec, R_mode="random", path=serq.PATH_SKINNY, groupm=waves // 4, check_pack=False)
+    _run_layer(spec, R_mode="random", path=serq.PATH_SKINNY, groupm=waves // 4, splitk=2, check_pack=False)
+
+
 @pytest.mark.parametrize("abits", [4, 8])
 @pytest.mark.parametrize("M,N,K", [(1, 32, 64), (40, 96, 192), (256, 256, 512), (300, 288, 448), (513, 544, 1088),
                                    (700, 320, 1024), (257, 32, 256), (64, 800, 2560), (33, 64, 128), (90, 160, 832)])
@@ -197,7 +227,7 @@ def test_gemm_extreme_codes_no_overflow():
 # ---------------------------------------------------------------------------
 # the fused layer
 # ---------------------------------------------------------------------------
-def _run_layer(spec, R_mode="random", path=serq.PATH_AUTO, rows=None, splitk=0, check_pack=True):
+def _run_layer(spec, R_mode="random", path=serq.PATH_AUTO, rows=None, splitk=0, check_pack=True, groupm=0):
     want = ("X", "s", "W", "R") if R_mode == "random" else ("X", "s", "W")
     L = workloads.make_layer(spec, want=want)
     O = oracle_layer(spec, L, R_mode=R_mode, rows=rows)
@@ -221,7 +251,7 @@ def _run_layer(spec, R_mode="random", path=serq.PATH_AUTO, rows=None, splitk=0, 
     else:
         Rp = None
     ws = serq.workspace(spec.M, spec.N, spec.K, spec.r, spec.abits, DEV)
-    fl = serq.flags(path, splitk=splitk)
+    fl = serq.flags(path, splitk=splitk, groupm=groupm)
     acc = serq.gemm_i32(Xq, spec.abits, pk.Wq, spec.M, spec.N, spec.K, ws=ws, flags_=fl).cpu().numpy()
     acc_o = orc.gemm_i32(O.Xq, O.pk["Wq"])
     assert np.array_equal(acc[sel], acc_o)
