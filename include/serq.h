@@ -57,7 +57,7 @@ extern "C" {
 /* bits 8..15 of `flags`: split-K factor override for the skinny path (0 = auto) */
 #define SERQ_FLAG_SPLITK(n) (((n) & 0xff) << 8)
 /* bits 16..19 of `flags`: MFMA path: token-tile group height of the block order (0 = auto);
- * skinny path: waves per workgroup / 4 (1, 2 or 4; anything else = auto) */
+ * skinny path: waves per workgroup / 4 (1 or 2; anything else = auto) */
 #define SERQ_FLAG_GROUPM(n) (((n) & 0xf) << 16)
 /* bits 20..30 of `flags`: number of column tiles of the MFMA path (0 = auto; clamped to the valid range) */
 #define SERQ_FLAG_COLTILES(n) (((n) & 0x7ff) << 20)

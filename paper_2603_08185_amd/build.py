@@ -12,6 +12,9 @@ SOURCES = ["api.hip", "quantize_act.hip", "pack.hip", "skinny.hip", "gemm_mfma.h
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # kernels that take their first arguments one by one get them preloaded into SGPRs by the
+    # dispatcher instead of fetching them with a scalar load (0.25 us on a 6 us decode launch)
+    "-mllvm", "-amdgpu-kernarg-preload-count=12",
     "-Wno-unused-command-line-argument", "-Wno-inline-asm",
 ]
 

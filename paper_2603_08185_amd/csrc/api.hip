@@ -164,7 +164,7 @@ static int linear_common(LinearArgs& a, int64_t M, int64_t N, int64_t K, int fla
   a.M = (int)M; a.N = (int)N; a.K = (int)K;
   a.splitk = (flags >> 8) & 0xff;
   a.groupm = (flags >> 16) & 0xf;
-  a.skinny_waves = a.groupm * 4;                     // the two paths share the field: 1, 2, 4 -> 4, 8, 16 waves
+  a.skinny_waves = a.groupm * 4;                     // the two paths share the field: 1, 2 -> 4, 8 waves
   a.coltiles = (flags >> 20) & 0x7ff;
   const int path = flags & 0xff;
   if (path != SERQ_PATH_AUTO && path != SERQ_PATH_SKINNY && path != SERQ_PATH_MFMA) return SERQ_EUNSUPPORTED;

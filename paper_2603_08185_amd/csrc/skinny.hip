@@ -93,7 +93,10 @@ struct Stage {
 };
 
 template <int ABITS, int kWaves, int kGroup>
-__global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGroup == 8 ? 4 : 5, 8))) void serq_skinny_kernel(const SkinnyParams p) {
+__global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGroup == 8 ? 4 : 5, 8))) void serq_skinny_kernel(
+    // needed before the first load is issued: passed one by one so that the dispatcher can preload them into SGPRs
+    const uint8_t* hXq, const u4* hWq, int hK, int hM, int kb_per, int kb_rem, int hregion,
+    const SkinnyParams p) {
   constexpr int kThreads = kWaves * 64;
   constexpr int SH = (ABITS == 8) ? 4 : 8;
   typedef Stage<ABITS, kGroup> S;
@@ -102,17 +105,16 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGr
   const int tid = threadIdx.x;
   const int w = tid >> 6, l = tid & 63;
   const int m = l & 31, g = l >> 5;
-  const int nb = blockIdx.x / p.splitk;
-  const int ks = blockIdx.x - nb * p.splitk;
-  const int KB = p.K >> 6;
-  const int kb0 = (int)(((int64_t)KB * ks) / p.splitk);
-  const int kb1 = (int)(((int64_t)KB * (ks + 1)) / p.splitk);
-  const size_t rowbytes = (size_t)p.K * ABITS / 8;
+  const int nb = blockIdx.x, ks = blockIdx.y;          // grid: (channel blocks, K slices)
+  const int KB = hK >> 6;
+  const int kb0 = ks * kb_per + (ks < kb_rem ? ks : kb_rem);   // the first kb_rem slices are one fragment longer
+  const int kb1 = kb0 + kb_per + (ks < kb_rem ? 1 : 0);
+  const size_t rowbytes = (size_t)hK * ABITS / 8;
 
-  const bool mv = m < p.M;
-  const uint8_t* xrow = p.Xq + (size_t)(mv ? m : 0) * rowbytes;
-  const u4* wfr = p.Wq + (size_t)nb * KB * 64 + l;
-  uint8_t* my = lds + (size_t)w * p.region;
+  const bool mv = m < hM;
+  const uint8_t* xrow = hXq + (size_t)(mv ? m : 0) * rowbytes;
+  const u4* wfr = hWq + (size_t)nb * KB * 64 + l;
+  uint8_t* my = lds + (size_t)w * hregion;
 
   v16i acc;
 #pragma unroll
@@ -145,7 +147,7 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGr
   for (int q = 0; q < NQ; ++q) {
     const int id = tid + q * kThreads;
     sc_m[q] = sc_n[q] = 0.0f;
-    if (p.acc_out == nullptr && p.splitk == 1 && (id >> 5) < p.M) {
+    if (p.acc_out == nullptr && gridDim.y == 1 && (id >> 5) < hM) {
       sc_m[q] = p.scale[id >> 5];
       sc_n[q] = p.wscale[nb * 32 + (id & 31)];
     }
@@ -157,7 +159,7 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGr
   // staging role of this lane: row srow0 + RPI*j of instruction j, slot l % P of the row
   const int srow0 = l / S::P, slot = l % S::P;
   const int nfr = kb1 - kb0;                            // fragments in the slice
-  const uint8_t* xslice = p.Xq + (size_t)kb0 * S::FB;
+  const uint8_t* xslice = hXq + (size_t)kb0 * S::FB;
   const uint32_t my_lds = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_addr(my));
 #pragma unroll 1
   for (int gi = w; gi * kGroup < nfr; gi += kWaves) {
@@ -165,9 +167,9 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGr
     // token rows of the group straight into LDS, whole lines, ahead of the weight loads
 #pragma unroll
     for (int j = 0; j < S::NI; ++j) {
-      if (S::RPI * j < p.M) {                           // uniform
+      if (S::RPI * j < hM) {                           // uniform
         const int row = srow0 + S::RPI * j;
-        const int rowc = row < p.M ? row : p.M - 1;     // rows past M: any valid address, never read back
+        const int rowc = row < hM ? row : hM - 1;     // rows past M: any valid address, never read back
         int col = f0 * S::FB + ((slot ^ S::sw(row)) << 4);
         col = col < nfr * S::FB ? col : 0;              // pieces past a ragged slice likewise
         dma16(xslice, (uint32_t)rowc * (uint32_t)rowbytes + (uint32_t)col, my_lds + 1024u * j);
@@ -234,7 +236,7 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGr
   // half h, token t at word (2e + h) * Mp + t, the fp32 partials 32*Mp words
   // further; the odd pitch Mp spreads the gather over the banks.
   // Thread tid finishes (token q/32, channel q%32) for q = tid, tid + kThreads, ...
-  const int Mp = p.M | 1;
+  const int Mp = hM | 1;
   const int nwl = JB < kWaves ? JB : kWaves;              // waves that hold low-rank sums
   if (mv) {
     int* red = reinterpret_cast<int*>(my);
@@ -251,14 +253,14 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGr
   for (int q = 0; q < NQ; ++q) {
     const int id = tid + q * kThreads;
     const int nl = id & 31, mt = id >> 5;
-    if (mt >= p.M) continue;
+    if (mt >= hM) continue;
     const int src = (2 * (4 * (nl >> 3) + (nl & 3)) + ((nl >> 2) & 1)) * Mp + mt;
     int tot_i = 0;
     float tot_f = 0.0f;
 #pragma unroll
-    for (int ww = 0; ww < kWaves; ++ww) tot_i += *reinterpret_cast<const int*>(lds + (size_t)ww * p.region + 4 * src);
+    for (int ww = 0; ww < kWaves; ++ww) tot_i += *reinterpret_cast<const int*>(lds + (size_t)ww * hregion + 4 * src);
     if (lr_here)
-      for (int ww = 0; ww < nwl; ++ww) tot_f += *reinterpret_cast<const float*>(lds + (size_t)ww * p.region + 4 * (32 * Mp + src));
+      for (int ww = 0; ww < nwl; ++ww) tot_f += *reinterpret_cast<const float*>(lds + (size_t)ww * hregion + 4 * (32 * Mp + src));
     if (p.splitk > 1) {
       // partial sums of this slice; the reduce kernel finishes the job
       p.part_i[((size_t)nb * p.splitk + ks) * 1024 + id] = tot_i;
@@ -292,7 +294,7 @@ int skinny_splitk_auto(int M, int N, int K) {
   (void)M;
   const int nblk = N / 32;
   const int KB = K / 64;
-  int s = (128 + nblk - 1) / nblk;           // 128 sixteen-wave workgroups already keep the memory system busy; a split costs a second launch
+  int s = (128 + nblk - 1) / nblk;           // 128 workgroups already keep half the CUs streaming; a split costs a second launch
   const int smax = KB / 16 > 0 ? KB / 16 : 1;          // keep >= 16 fragments per slice
   if (s > smax) s = smax;
   if (s > 16) s = 16;
@@ -352,8 +354,8 @@ int launch_skinny(const LinearArgs& a, hipStream_t st) {
   p.region = region;
   const size_t lds_bytes = (size_t)region * nw;
 
-  dim3 grid((unsigned)(nblk * splitk)), block((unsigned)nw * 64);
-#define SERQ_SKINNY_LAUNCH(AB, NW, G) hipLaunchKernelGGL((serq_skinny_kernel<AB, NW, G>), grid, block, lds_bytes, st, p)
+  dim3 grid((unsigned)nblk, (unsigned)splitk), block((unsigned)nw * 64);
+#define SERQ_SKINNY_LAUNCH(AB, NW, G) hipLaunchKernelGGL((serq_skinny_kernel<AB, NW, G>), grid, block, lds_bytes, st, p.Xq, p.Wq, p.K, p.M, KB / splitk, KB % splitk, p.region, p)
   if (a.abits == 8) {
     if (nw == 4) { if (grp == 4) SERQ_SKINNY_LAUNCH(8, 4, 4); else SERQ_SKINNY_LAUNCH(8, 4, 8); }
     else { if (grp == 4) SERQ_SKINNY_LAUNCH(8, 8, 4); else SERQ_SKINNY_LAUNCH(8, 8, 8); }
