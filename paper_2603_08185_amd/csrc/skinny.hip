@@ -70,6 +70,8 @@ __device__ __forceinline__ void finish(const SkinnyParams& p, int m, int n, int 
 }
 
 
+constexpr int kRedPitch = 36;           // words per token row of a wave's parked partial sums
+
 __device__ __forceinline__ uint32_t lds_addr(const void* ptr) {
   return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)ptr;
 }
@@ -230,22 +232,24 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGr
   }
 
   // ---- combine the waves ----------------------------------------------------
-  // accumulator register e of lane l holds channel 8*(e/4) + 4*(l/32) + e%4 of
-  // the block and token l%32; only tokens < M are exchanged.  A wave parks its
-  // partials in its own region (dead as token staging by now): register e, lane
-  // half h, token t at word (2e + h) * Mp + t, the fp32 partials 32*Mp words
-  // further; the odd pitch Mp spreads the gather over the banks.
+  // accumulator registers 4i..4i+3 of lane l hold channels 8i + 4*(l/32) + 0..3 of
+  // the block for token l%32; only tokens < M are exchanged.  A wave parks its
+  // partials in its own region (dead as token staging by now) as [token][channel]
+  // rows of kRedPitch words -- four 16-byte writes per lane, and a pitch of 9
+  // bank groups keeps both the writes and the gather conflict-free -- with the
+  // fp32 partials M rows further.
   // Thread tid finishes (token q/32, channel q%32) for q = tid, tid + kThreads, ...
-  const int Mp = hM | 1;
   const int nwl = JB < kWaves ? JB : kWaves;              // waves that hold low-rank sums
   if (mv) {
-    int* red = reinterpret_cast<int*>(my);
+    int* red = reinterpret_cast<int*>(my) + m * kRedPitch + 4 * g;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) red[(2 * e + g) * Mp + m] = acc[e];
+    for (int i = 0; i < 4; ++i)
+      *reinterpret_cast<v4i*>(red + 8 * i) = (v4i){acc[4 * i], acc[4 * i + 1], acc[4 * i + 2], acc[4 * i + 3]};
     if (lr_here && w < nwl) {
-      float* redf = reinterpret_cast<float*>(my) + 32 * Mp;
+      float* redf = reinterpret_cast<float*>(red + hM * kRedPitch);
 #pragma unroll
-      for (int e = 0; e < 16; ++e) redf[(2 * e + g) * Mp + m] = accf[e];
+      for (int i = 0; i < 4; ++i)
+        *reinterpret_cast<v4f*>(redf + 8 * i) = (v4f){accf[4 * i], accf[4 * i + 1], accf[4 * i + 2], accf[4 * i + 3]};
     }
   }
   __syncthreads();
@@ -254,13 +258,13 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGr
     const int id = tid + q * kThreads;
     const int nl = id & 31, mt = id >> 5;
     if (mt >= hM) continue;
-    const int src = (2 * (4 * (nl >> 3) + (nl & 3)) + ((nl >> 2) & 1)) * Mp + mt;
+    const int src = mt * kRedPitch + nl;
     int tot_i = 0;
     float tot_f = 0.0f;
 #pragma unroll
     for (int ww = 0; ww < kWaves; ++ww) tot_i += *reinterpret_cast<const int*>(lds + (size_t)ww * hregion + 4 * src);
     if (lr_here)
-      for (int ww = 0; ww < nwl; ++ww) tot_f += *reinterpret_cast<const float*>(lds + (size_t)ww * hregion + 4 * (32 * Mp + src));
+      for (int ww = 0; ww < nwl; ++ww) tot_f += *reinterpret_cast<const float*>(lds + (size_t)ww * hregion + 4 * (hM * kRedPitch + src));
     if (p.splitk > 1) {
       // partial sums of this slice; the reduce kernel finishes the job
       p.part_i[((size_t)nb * p.splitk + ks) * 1024 + id] = tot_i;
@@ -346,9 +350,8 @@ int launch_skinny(const LinearArgs& a, hipStream_t st) {
   const int rpi = 1024 / rowb;
   const int rows = (a.M + rpi - 1) / rpi * rpi;
   const bool has_lr = p.r > 0 && p.acc_out == nullptr;
-  const int Mp = a.M | 1;
   int region = rows * rowb;
-  const int red = (has_lr ? 2 : 1) * 32 * Mp * 4;
+  const int red = (has_lr ? 2 : 1) * a.M * kRedPitch * 4;
   if (red > region) region = red;
   region = (region + 15) & ~15;
   p.region = region;
