@@ -211,6 +211,21 @@ def test_gemm_i32_mfma(abits, M, N, K):
         assert torch.equal(sk, got)
 
 
+@pytest.mark.parametrize("abits", [4, 8])
+@pytest.mark.parametrize("coltiles", [1, 2, 3, 5, 7, 13, 25, 2047])
+def test_gemm_i32_mfma_column_tiling_override(abits, coltiles):
+    # N = 25 blocks of 32 channels: every way of cutting them into column tiles (clamped to 4 .. 25 tiles of at
+    # most 8 blocks) and every group height must give the same exact accumulators
+    M, N, K = 300, 800, 640
+    Xq, Wq = _codes(M, K, N, abits, seed=coltiles)
+    pk, xq, _ = _device_codes(Xq, Wq, abits)
+    want = orc.gemm_i32(Xq, Wq)
+    for groupm in (0, 1, 3):
+        fl = serq.flags(serq.PATH_MFMA, groupm=groupm, coltiles=coltiles)
+        got = serq.gemm_i32(xq, abits, pk.Wq, M, N, K, flags_=fl)
+        assert np.array_equal(got.cpu().numpy(), want), f"groupm={groupm}"
+
+
 def test_gemm_extreme_codes_no_overflow():
     # every product at its maximum magnitude over a long K
     for abits in (4, 8):
