@@ -17,6 +17,7 @@ the launches are replayed from a HIP graph, as a serving loop would issue them.
 `cpu_baseline` is the NumPy oracle timed on whole passes (about 10 s) over the same
 workload on this host's cores.
 
+`--sweep` times every benchmark configuration instead (one JSON line per row).
 `--calibrate-copy` runs nothing but a plain device copy of a known size; it
 exists so that the FETCH_SIZE / WRITE_SIZE counters of a profiler run of this
 script can be scaled to bytes.
@@ -183,6 +184,81 @@ def cpu_baseline(L, n_tokens: int = 4096, min_seconds: float = 10.0):
                       f"(quantize_act + gemm + epilogue), {dt:.1f} s", "host_cpus": len(os.sched_getaffinity(0))}, Y
 
 
+def _time_launches(fn, n: int, reps: int = 3) -> float:
+    """Best-of-reps average time of n back-to-back launches of fn(i), in microseconds."""
+    best = float("inf")
+    for _ in range(reps):
+        e0, e1 = _events(2)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        best = min(best, e0.elapsed_time(e1) * 1e3 / n)
+    return best
+
+
+def sweep():
+    """Every benchmark configuration, one JSON line each: quantize_act and serq_linear timed separately
+    (HIP events around back-to-back launches; decode-sized shapes rotate over copies of the weights that
+    together exceed the Infinity Cache), with the roofline that bounds the row."""
+    dev = "cuda:0"
+    rows = [workloads.config2()]
+    rows += [workloads.config3(w, M) for w in ("up", "down") for M in (1, 16, 256, 4096)]
+    rows += [workloads.config4(M) for M in (1, 4, 32)]
+    rows += [workloads.config5(layer, r) for layer in workloads.config5_layers() for r in (0, 32, 64, 128, 256)]
+    cache = {}
+    for spec in rows:
+        key = (spec.cfg, spec.N, spec.K, spec.abits, spec.seed_index)
+        if key not in cache:                        # weights depend on the layer, not on M or r
+            cache.clear()
+            L = workloads.make_layer(spec, want=("s", "W"))
+            cache[key] = serq.pack_weights(L["W"].to(dev), L["s"].to(dev), 0, want_R=False, want_Rp=False)
+        pk = cache[key]
+        M, N, K, r = spec.M, spec.N, spec.K, spec.r
+        X = workloads.make_layer(spec, want=("X",))["X"]
+        Xhat = workloads.permute_channels(X, pk.perm.cpu().numpy()).to(dev)
+        Rp = None
+        if r:
+            g = torch.Generator().manual_seed(1000 * spec.cfg + 7)
+            Rp = serq.pack_lowrank((torch.randn((r, N), generator=g) * 0.01).to(torch.bfloat16).to(dev))
+        Xq = torch.empty(M * K * spec.abits // 8, dtype=torch.uint8, device=dev)
+        scale = torch.empty(M, dtype=torch.float32, device=dev)
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        ws = serq.workspace(M, N, K, r, spec.abits, dev)
+        small = M <= 32
+        ncopy = 1
+        if small:
+            per_copy = pk.Wq.numel() + (Rp.numel() if Rp is not None else 0)
+            ncopy = int(np.ceil(640e6 / per_copy))
+        Wqs = [pk.Wq] + [pk.Wq.clone() for _ in range(ncopy - 1)]
+        Rps = [Rp] + [Rp.clone() if Rp is not None else None for _ in range(ncopy - 1)]
+        n = max(20, 2 * ncopy)
+
+        def q(i):
+            serq.quantize_act(Xhat, pk.s_inv, spec.abits, Xq=Xq, scale=scale)
+
+        def lin(i):
+            j = i % ncopy
+            serq.linear(Xq, scale, spec.abits, Wqs[j], pk.wscale, M, N, K, Rp=Rps[j], r=r, Y=Y, ws=ws)
+
+        q(0); lin(0)
+        q_us = _time_launches(q, n)
+        l_us = _time_launches(lin, n)
+        row = {"workload": spec.name, "abits": spec.abits, "M": M, "K": K, "N": N, "r": r,
+               "quantize_act_us": round(q_us, 2), "serq_linear_us": round(l_us, 2), "layer_us": round(q_us + l_us, 2)}
+        if small:
+            b = decode_bytes(spec)
+            row.update({"bound": "hbm", "gbs": round(b / l_us / 1e3, 1), "frac": round(b / l_us / 1e3 / HBM_PEAK_GBS, 4)})
+        else:
+            ops = 2.0 * M * N * K
+            row.update({"bound": "mfma", "tops": round(ops / l_us / 1e6, 1),
+                        "frac": round(ops / l_us / 1e6 / INT8_PEAK_TOPS, 4)})
+        print(json.dumps(row), flush=True)
+        del Wqs, Rps
+
+
 def calibrate_copy(nbytes: int = 1 << 30, reps: int = 3):
     src = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").fill_(1)
     dst = torch.empty_like(src)
@@ -200,6 +276,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the M=1 decode leg")
     ap.add_argument("--calibrate-copy", action="store_true", help="only run a plain 1 GiB device copy (counter calibration)")
+    ap.add_argument("--sweep", action="store_true", help="time every benchmark configuration (one JSON line per row) instead of the headline step")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -210,6 +287,9 @@ def main():
     serq.lib()
     if a.calibrate_copy:
         calibrate_copy()
+        return
+    if a.sweep:
+        sweep()
         return
 
     pre = bench_prefill(a.steps, a.warmup)
