@@ -184,15 +184,26 @@ def cpu_baseline(L, n_tokens: int = 4096, min_seconds: float = 10.0):
                       f"(quantize_act + gemm + epilogue), {dt:.1f} s", "host_cpus": len(os.sched_getaffinity(0))}, Y
 
 
-def _time_launches(fn, n: int, reps: int = 3) -> float:
-    """Best-of-reps average time of n back-to-back launches of fn(i), in microseconds."""
+def _time_launches(fn, n: int, reps: int = 3, graph: bool = False) -> float:
+    """Best-of-reps average time of n back-to-back launches of fn(i), in microseconds.  With graph=True the
+    n launches are captured once and replayed (short kernels: the Python call costs more than the launch)."""
+    run = lambda: [fn(i) for i in range(n)]
+    if graph:
+        side = torch.cuda.Stream()
+        g = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                run()
+        torch.cuda.synchronize()
+        g.replay()
+        run = g.replay
     best = float("inf")
     for _ in range(reps):
         e0, e1 = _events(2)
         torch.cuda.synchronize()
         e0.record()
-        for i in range(n):
-            fn(i)
+        run()
         e1.record()
         torch.cuda.synchronize()
         best = min(best, e0.elapsed_time(e1) * 1e3 / n)
@@ -202,7 +213,7 @@ def _time_launches(fn, n: int, reps: int = 3) -> float:
 def sweep():
     """Every benchmark configuration, one JSON line each: quantize_act and serq_linear timed separately
     (HIP events around back-to-back launches; decode-sized shapes rotate over copies of the weights that
-    together exceed the Infinity Cache), with the roofline that bounds the row."""
+    together exceed the Infinity Cache and are replayed from a HIP graph), with the roofline that bounds the row."""
     dev = "cuda:0"
     rows = [workloads.config2()]
     rows += [workloads.config3(w, M) for w in ("up", "down") for M in (1, 16, 256, 4096)]
@@ -244,8 +255,8 @@ def sweep():
             serq.linear(Xq, scale, spec.abits, Wqs[j], pk.wscale, M, N, K, Rp=Rps[j], r=r, Y=Y, ws=ws)
 
         q(0); lin(0)
-        q_us = _time_launches(q, n)
-        l_us = _time_launches(lin, n)
+        q_us = _time_launches(q, n, graph=small)
+        l_us = _time_launches(lin, n, graph=small)
         row = {"workload": spec.name, "abits": spec.abits, "M": M, "K": K, "N": N, "r": r,
                "quantize_act_us": round(q_us, 2), "serq_linear_us": round(l_us, 2), "layer_us": round(q_us + l_us, 2)}
         if small:

@@ -20,7 +20,9 @@ vector, P the saliency permutation, R the single compensation matrix [r, N].
 Pins (tests/test_oracle_*.py): hand-worked tiny layer, the integer-layer
 reduction to a textbook matmul, the scale/2 rounding bound, permutation and
 flattening invariances, the r = 0 reduction, and the exact-residual identity
-main + compensation == Q(X) . [W_s ; deq(Q(W_r))].  No function is unpinned.
+main + compensation == Q(X) . [W_s ; deq(Q(W_r))]; for the 4-bit compensation
+matrix a hand-worked example, the integer-matrix reduction, the scale/2 bound
+and the reduction to `linear` with the dequantised matrix.  No function is unpinned.
 """
 from __future__ import annotations
 
@@ -158,6 +160,45 @@ def linear(Xq, scale, Wq, wscale, R=None, s_begin: int = 0, acc=None) -> np.ndar
     y = np.asarray(wscale, np.float64)[None, :] * acc.astype(np.float64)
     if R is not None and R.shape[0] > 0:
         y = y + lowrank(Xq, R, s_begin)
+    return np.asarray(scale, np.float64)[:, None] * y
+
+
+def quantize_lowrank(R: np.ndarray):
+    """Q(R): the compensation matrix itself on the INT4 grid (Sec. 3.2, second line of Eq. 7).
+
+    R [r, N] holds the values actually stored (fp16/bf16 widened exactly).  The
+    grid is the weights' one, Eq. 1 per output channel n (a column of R here):
+      rscale[n] = max_j |R[j,n]| / 7              (fp32 division; 1.0 for a zero column)
+      Rq[j,n]   = clip(rne(R[j,n] / rscale[n]), -7, 7)
+    Returns (Rq int8 [r, N], rscale fp32 [N]).
+    """
+    R = np.asarray(R, dtype=F32)
+    r, N = R.shape
+    amax = np.max(np.abs(R), axis=0).astype(F32) if r else np.zeros(N, F32)
+    rscale = np.where(amax > 0, amax / F32(7), F32(1.0)).astype(F32)
+    Rq = np.clip(np.rint((R / rscale[None, :]).astype(F32)), -7, 7).astype(np.int8)
+    return Rq, rscale
+
+
+def lowrank_i32(Xq: np.ndarray, Rq: np.ndarray, s_begin: int = 0) -> np.ndarray:
+    """acc_r[m,n] = sum_{j<r} Xq[m, s_begin+j] * Rq[j,n], exact (integer form of the second term of Eq. 7)."""
+    r = Rq.shape[0]
+    a = Xq[:, s_begin:s_begin + r].astype(np.int64) @ Rq.astype(np.int64)
+    assert r * 128 * 8 < 2 ** 31
+    return a.astype(np.int32)
+
+
+def linear_q4r(Xq, scale, Wq, wscale, Rq, rscale, s_begin: int = 0, acc=None) -> np.ndarray:
+    """Y[m,n] = scale[m] * ( wscale[n] * acc[m,n] + rscale[n] * acc_r[m,n] )  in fp64.
+
+    The all-low-precision form of Eq. 7 (second line): both products are integer
+    GEMMs and each is dequantised by its own per-output-channel scale.
+    """
+    if acc is None:
+        acc = gemm_i32(Xq, Wq)
+    acc_r = lowrank_i32(Xq, Rq, s_begin)
+    y = (np.asarray(wscale, np.float64)[None, :] * acc.astype(np.float64)
+         + np.asarray(rscale, np.float64)[None, :] * acc_r.astype(np.float64))
     return np.asarray(scale, np.float64)[:, None] * y
 
 

@@ -242,3 +242,69 @@ def test_T11_effective_weight_bits():
     # 8-bit low-rank factors of the same parameter count (Table 1, "4.35" for the two-factor baseline)
     eff8 = sum(orc.effective_weight_bits(k, n, 128, group=128, r_bits=8) * k * n for k, n in layers) / tot
     assert 4.33 <= eff8 <= 4.355
+
+
+# ---------------------------------------------------------------------------
+# the 4-bit compensation matrix Q(R) (Eq. 7, second line)
+# ---------------------------------------------------------------------------
+def test_q4r_hand_worked_example():
+    g = _read_golden(os.path.join(HERE, "golden", "tiny_lowrank_q4.txt"))
+    Rq, rscale = orc.quantize_lowrank(g["R"])
+    assert np.array_equal(rscale, g["rscale"][0].astype(np.float32))
+    assert np.array_equal(Rq, g["Rq"].astype(np.int8))
+    Xq = g["Xq"].astype(np.int8)
+    assert np.array_equal(orc.lowrank_i32(Xq, Rq), g["acc_r"].astype(np.int32))
+    Y = orc.linear_q4r(Xq, g["scale"][0], None, g["wscale"][0], Rq, rscale, acc=g["acc"].astype(np.int32))
+    assert np.array_equal(Y, g["Y"])
+
+
+def test_q4r_integer_matrix_is_textbook_matmul():
+    # R integer-valued in [-7, 7] with a +-7 in every column: rscale = 1, codes = R, and the whole
+    # layer is two textbook integer matrix products
+    rng = np.random.default_rng(5)
+    M, K, N, r, s_begin = 5, 96, 7, 48, 32
+    R = rng.integers(-7, 8, size=(r, N))
+    R[rng.integers(0, r, size=N), np.arange(N)] = rng.choice([-7, 7], size=N)
+    Rq, rscale = orc.quantize_lowrank(R.astype(np.float32))
+    assert np.all(rscale == 1.0) and np.array_equal(Rq, R.astype(np.int8))
+    Xq = rng.integers(-7, 8, size=(M, K)).astype(np.int8)
+    Wq = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
+    Y = orc.linear_q4r(Xq, np.ones(M, np.float32), Wq, np.ones(N, np.float32), Rq, rscale, s_begin=s_begin)
+    want = Xq.astype(np.int64) @ Wq.astype(np.int64).T + Xq[:, s_begin:s_begin + r].astype(np.int64) @ R
+    assert np.array_equal(Y, want.astype(np.float64))
+    # brute force over the definition
+    acc_r = orc.lowrank_i32(Xq, Rq, s_begin)
+    for m in range(M):
+        for n in range(N):
+            assert acc_r[m, n] == sum(int(Xq[m, s_begin + j]) * int(R[j, n]) for j in range(r))
+
+
+def test_q4r_rounding_bound_and_extremes():
+    rng = np.random.default_rng(6)
+    R = (rng.standard_normal((64, 40)) * 0.01).astype(np.float32)
+    R[:, 3] = 0.0
+    Rq, rscale = orc.quantize_lowrank(R)
+    assert rscale[3] == 1.0 and not Rq[:, 3].any()
+    assert np.max(np.abs(Rq)) <= 7
+    err = np.abs(R.astype(np.float64) - rscale.astype(np.float64)[None, :] * Rq)
+    assert np.all(err <= rscale.astype(np.float64)[None, :] * (0.5 + 1e-6))
+    cols = np.arange(40) != 3
+    jmax = np.argmax(np.abs(R), axis=0)
+    assert np.all(np.abs(Rq[jmax, np.arange(40)])[cols] == 7)
+
+
+def test_q4r_reduces_to_linear_with_the_dequantised_matrix():
+    # rscale * Rq is a matrix like any other: the 16-bit-R routine fed with it must agree up to fp64 rounding
+    spec = workloads.LayerSpec("pin", 1, 8, 6, 128, 24, 32, "bf16", "bf16", 2, 20.0, 20.0)
+    L = workloads.make_layer(spec)
+    pk = orc.pack_weights(L["W"].float().numpy(), L["s"].numpy(), spec.r)
+    Xq, scale = orc.quantize_act(L["X"].float().numpy()[:, pk["perm"]], pk["s_inv"], spec.abits)
+    Rq, rscale = orc.quantize_lowrank(L["R"].float().numpy())
+    Ya = orc.linear_q4r(Xq, scale, pk["Wq"], pk["wscale"], Rq, rscale)
+    Yb = orc.linear(Xq, scale, pk["Wq"], pk["wscale"], rscale.astype(np.float64)[None, :] * Rq)
+    assert np.allclose(Ya, Yb, rtol=1e-12, atol=0.0)
+    # and quantising the compensation matrix moves the output by at most what the half-step bound allows
+    Y16 = orc.linear(Xq, scale, pk["Wq"], pk["wscale"], L["R"].double().numpy())
+    bound = scale.astype(np.float64)[:, None] * (np.abs(Xq[:, :spec.r]).sum(axis=1)[:, None]
+                                                 * rscale.astype(np.float64)[None, :] * 0.5)
+    assert np.all(np.abs(Ya - Y16) <= bound * (1 + 1e-6) + 1e-12)
