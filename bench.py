@@ -8,6 +8,10 @@ GEMM with the rank-128 compensation and the dequantising epilogue fused).
 Workload: the up projection of the MLP pair, W4A8, M = 4096 tokens,
 K = 4096 -> N = 11008, r = 128, bf16 in / bf16 out.
 
+Before anything is timed the step runs untimed for 0.15 s: coming out of idle the
+part takes about 40 ms of load to reach its sustained clocks, and a 50-step run
+would otherwise sit entirely inside that ramp.
+
 Prints ONE JSON line.  `value` is 2*M*N*K / step time in TOPS.  `roofline`
 prices the dominant kernel (serq_linear) against the int8 MFMA peak using its
 own launch durations, measured with HIP events on the launch stream inside the
@@ -53,6 +57,17 @@ def _events(n):
     return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
 
 
+def spin_up(fn, seconds: float = 0.15):
+    """Untimed load before any measurement: after idling, the part needs about 40 ms of work to reach its
+    sustained clocks (the first 20 ms of this benchmark's step run 25 % slower than the steady state)."""
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(20):
+            fn()
+        torch.cuda.synchronize()
+
+
 def bench_prefill(steps: int, warmup: int):
     spec = workloads.config3("up", 4096)
     L = workloads.make_layer(spec)
@@ -69,6 +84,7 @@ def bench_prefill(steps: int, warmup: int):
         serq.quantize_act(Xhat, pk.s_inv, spec.abits, Xq=Xq, scale=scale)
         serq.linear(Xq, scale, spec.abits, pk.Wq, pk.wscale, M, N, K, Rp=Rp, r=spec.r, Y=Y)
 
+    spin_up(step)
     for _ in range(warmup):
         step()
     ev = _events(2 * steps + 1)
@@ -135,8 +151,7 @@ def bench_decode(L, pk, reps: int = 5):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
 
-    launches(True)
-    torch.cuda.synchronize()
+    spin_up(lambda: launches(True), 0.05)
     side = torch.cuda.Stream()          # graph capture needs a non-default stream (default priority)
     graphs = {}
     for rotate in (True, False):
@@ -146,6 +161,7 @@ def bench_decode(L, pk, reps: int = 5):
                 launches(rotate)
         graphs[rotate] = g
     torch.cuda.synchronize()
+    spin_up(graphs[True].replay, 0.05)
     for g in graphs.values():
         g.replay()
     cold = min(timed(graphs[True].replay) for _ in range(reps))
@@ -230,10 +246,12 @@ def sweep():
         M, N, K, r = spec.M, spec.N, spec.K, spec.r
         X = workloads.make_layer(spec, want=("X",))["X"]
         Xhat = workloads.permute_channels(X, pk.perm.cpu().numpy()).to(dev)
-        Rp = None
+        Rp = Rq = None
         if r:
             g = torch.Generator().manual_seed(1000 * spec.cfg + 7)
-            Rp = serq.pack_lowrank((torch.randn((r, N), generator=g) * 0.01).to(torch.bfloat16).to(dev))
+            Rh = (torch.randn((r, N), generator=g) * 0.01).to(torch.bfloat16).to(dev)
+            Rp = serq.pack_lowrank(Rh)
+            Rq = serq.pack_lowrank_q4(Rh)                 # the same matrix on the 4-bit grid (Eq. 7, second line)
         Xq = torch.empty(M * K * spec.abits // 8, dtype=torch.uint8, device=dev)
         scale = torch.empty(M, dtype=torch.float32, device=dev)
         Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
@@ -245,6 +263,7 @@ def sweep():
             ncopy = int(np.ceil(640e6 / per_copy))
         Wqs = [pk.Wq] + [pk.Wq.clone() for _ in range(ncopy - 1)]
         Rps = [Rp] + [Rp.clone() if Rp is not None else None for _ in range(ncopy - 1)]
+        Rqs = [Rq] + [Rq.clone() if Rq is not None else None for _ in range(ncopy - 1)]
         n = max(20, 2 * ncopy)
 
         def q(i):
@@ -254,11 +273,19 @@ def sweep():
             j = i % ncopy
             serq.linear(Xq, scale, spec.abits, Wqs[j], pk.wscale, M, N, K, Rp=Rps[j], r=r, Y=Y, ws=ws)
 
-        q(0); lin(0)
+        def lin_q4r(i):
+            j = i % ncopy
+            serq.linear(Xq, scale, spec.abits, Wqs[j], pk.wscale, M, N, K, Rp=Rqs[j], r=r, r_dtype=serq.I4, Y=Y, ws=ws)
+
+        spin_up(lambda: lin(0), 0.05)
+        q(0)
         q_us = _time_launches(q, n, graph=small)
         l_us = _time_launches(lin, n, graph=small)
         row = {"workload": spec.name, "abits": spec.abits, "M": M, "K": K, "N": N, "r": r,
                "quantize_act_us": round(q_us, 2), "serq_linear_us": round(l_us, 2), "layer_us": round(q_us + l_us, 2)}
+        if r:
+            lin_q4r(0)
+            row["serq_linear_q4r_us"] = round(_time_launches(lin_q4r, n, graph=small), 2)
         if small:
             b = decode_bytes(spec)
             row.update({"bound": "hbm", "gbs": round(b / l_us / 1e3, 1), "frac": round(b / l_us / 1e3 / HBM_PEAK_GBS, 4)})
@@ -267,7 +294,7 @@ def sweep():
             row.update({"bound": "mfma", "tops": round(ops / l_us / 1e6, 1),
                         "frac": round(ops / l_us / 1e6 / INT8_PEAK_TOPS, 4)})
         print(json.dumps(row), flush=True)
-        del Wqs, Rps
+        del Wqs, Rps, Rqs
 
 
 def calibrate_copy(nbytes: int = 1 << 30, reps: int = 3):
@@ -282,8 +309,8 @@ def calibrate_copy(nbytes: int = 1 << 30, reps: int = 3):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the M=1 decode leg")
     ap.add_argument("--calibrate-copy", action="store_true", help="only run a plain 1 GiB device copy (counter calibration)")

@@ -49,6 +49,8 @@ extern "C" {
 #define SERQ_F32  0
 #define SERQ_F16  1
 #define SERQ_BF16 2
+/* r_dtype of serq_linear only: the compensation matrix is the 4-bit blob of serq_pack_lowrank_q4 */
+#define SERQ_I4   3
 
 /* kernel selection for serq_linear / serq_gemm_i32 (low byte of `flags`) */
 #define SERQ_PATH_AUTO   0     /* by M: skinny for M <= 32, tiled MFMA above    */
@@ -69,6 +71,7 @@ const char* serq_strerror(int code);
 size_t serq_packed_act_bytes(int64_t M, int64_t K, int abits);     /* Xq                    */
 size_t serq_packed_weight_bytes(int64_t N, int64_t K);             /* Wq                    */
 size_t serq_packed_lowrank_bytes(int64_t N, int r);                /* Rp (16-bit elements)  */
+size_t serq_packed_lowrank_q4_bytes(int64_t N, int r);             /* Rq (4-bit codes + rscale) */
 size_t serq_workspace_bytes(int64_t M, int64_t N, int64_t K, int r, int abits);
 
 /* Zero a workspace before its first use.  serq_linear / serq_gemm_i32 leave it
@@ -110,6 +113,20 @@ int serq_pack_weights(const void* W, int w_dtype, const float* s, const int32_t*
  * packed form serq_linear reads (the single matrix of Eq. 5 / Eq. 7). */
 int serq_pack_lowrank(const void* R, int r_dtype, int64_t N, int r, void* Rp_out, void* stream);
 
+/*
+ * The compensation matrix itself on the INT4 grid (Sec. 3.2, Eq. 7, second
+ * line: "Q(R)").  R [r,N] fp16/bf16/fp32 (r_dtype) is quantised per output
+ * channel as the weights are (Eq. 1 over each column):
+ *   rscale[n] = max_j |R[j,n]| / 7 (1.0 for a zero column),
+ *   Rq[j,n]   = clip(rne(R[j,n] / rscale[n]), -7, 7),
+ * and laid out for serq_linear with r_dtype = SERQ_I4.  Rq_out takes
+ * serq_packed_lowrank_q4_bytes(N,r) bytes (codes in 64-rank fragments, ranks past
+ * r zero, followed by rscale [N] fp32).  r is a multiple of 16.
+ */
+int serq_pack_lowrank_q4(const void* R, int r_dtype, int64_t N, int r, void* Rq_out, void* stream);
+/* Canonical view of that blob: codes int8 [r,N] and rscale fp32 [N] (either may be NULL). */
+int serq_unpack_lowrank_q4(const void* Rq, int64_t N, int r, int8_t* codes_out, float* rscale_out, void* stream);
+
 /* Canonical views of the packed tensors (parity checks). */
 int serq_unpack_lowrank(const void* Rp, int64_t N, int r, void* R_out, void* stream);   /* 16-bit [r,N] */
 int serq_unpack_weights(const void* Wq, int64_t N, int64_t K, int8_t* Wq_i8_out, void* stream); /* [N,K] */
@@ -140,6 +157,13 @@ int serq_quantize_act(const void* X, int x_dtype, const float* s_inv,
  * with the integer sum exact in INT32 (int8 MFMA) and the rest in fp32; Y is
  * written once.  Rp is the packed compensation matrix (fp16 or bf16 per
  * r_dtype); r = 0 or Rp = NULL gives the plain W4A4 / W4A8 GEMM.
+ * With r_dtype = SERQ_I4, Rp is the blob of serq_pack_lowrank_q4 and the layer is
+ * the all-integer second line of Eq. 7,
+ *   Y[m,n] = scale[m] * ( wscale[n] * sum_k Xq[m,k]*Wq[n,k]
+ *                         + rscale[n] * sum_{j<r} Xq[m, s_begin+j] * Rq[j,n] ),
+ * both sums exact in INT32; the 64-rank fragments make the kernel read the token
+ * codes of channels s_begin .. s_begin + 64*ceil(r/64) - 1, which must exist
+ * (s_begin + 64*ceil(r/64) <= K; the codes past r meet zero weights).
  *   Y [M,N] in y_dtype (fp32/fp16/bf16), row stride ldy elements (multiple of 8).
  *   workspace: serq_workspace_bytes(...) bytes prepared by serq_workspace_init
  *   (needed only when the skinny path splits K; pass NULL/0 to forbid that).

@@ -17,7 +17,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libserq.so")
 
-F32, F16, BF16 = 0, 1, 2
+F32, F16, BF16, I4 = 0, 1, 2, 3
 PATH_AUTO, PATH_SKINNY, PATH_MFMA = 0, 1, 2
 
 _DT = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
@@ -30,11 +30,14 @@ SIGNATURES = {
     "serq_packed_act_bytes": (_sz, [_i64, _i64, _i]),
     "serq_packed_weight_bytes": (_sz, [_i64, _i64]),
     "serq_packed_lowrank_bytes": (_sz, [_i64, _i]),
+    "serq_packed_lowrank_q4_bytes": (_sz, [_i64, _i]),
     "serq_workspace_bytes": (_sz, [_i64, _i64, _i64, _i, _i]),
     "serq_workspace_init": (_i, [_vp, _sz, _vp]),
     "serq_pack_weights": (_i, [_vp, _i, _vp, _vp, _i64, _i64, _i, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp]),
     "serq_pack_lowrank": (_i, [_vp, _i, _i64, _i, _vp, _vp]),
     "serq_unpack_lowrank": (_i, [_vp, _i64, _i, _vp, _vp]),
+    "serq_pack_lowrank_q4": (_i, [_vp, _i, _i64, _i, _vp, _vp]),
+    "serq_unpack_lowrank_q4": (_i, [_vp, _i64, _i, _vp, _vp, _vp]),
     "serq_unpack_weights": (_i, [_vp, _i64, _i64, _vp, _vp]),
     "serq_unpack_act": (_i, [_vp, _i, _i64, _i64, _vp, _vp]),
     "serq_quantize_act": (_i, [_vp, _i, _vp, _i64, _i64, _i64, _i, _vp, _vp, _vp]),
@@ -157,6 +160,24 @@ def unpack_lowrank(Rp: torch.Tensor, N: int, r: int, dtype: torch.dtype) -> torc
     return out
 
 
+def pack_lowrank_q4(R: torch.Tensor) -> torch.Tensor:
+    """serq_pack_lowrank_q4: the compensation matrix [r,N] as 4-bit codes + per-channel scales."""
+    _dev(R, "R")
+    r, N = R.shape
+    L = lib()
+    Rq = torch.empty(max(L.serq_packed_lowrank_q4_bytes(N, r), 16), dtype=torch.uint8, device=R.device)
+    _check("serq_pack_lowrank_q4", L.serq_pack_lowrank_q4(_ptr(R), _DT[R.dtype], N, r, _ptr(Rq), _stream()))
+    return Rq
+
+
+def unpack_lowrank_q4(Rq: torch.Tensor, N: int, r: int):
+    codes = torch.empty((r, N), dtype=torch.int8, device=Rq.device)
+    rscale = torch.empty(N, dtype=torch.float32, device=Rq.device)
+    _check("serq_unpack_lowrank_q4",
+           lib().serq_unpack_lowrank_q4(_ptr(Rq), N, r, _ptr(codes), _ptr(rscale), _stream()))
+    return codes, rscale
+
+
 def unpack_weights(Wq: torch.Tensor, N: int, K: int) -> torch.Tensor:
     out = torch.empty((N, K), dtype=torch.int8, device=Wq.device)
     _check("serq_unpack_weights", lib().serq_unpack_weights(_ptr(Wq), N, K, _ptr(out), _stream()))
@@ -190,14 +211,16 @@ def quantize_act(X: torch.Tensor, s_inv: Optional[torch.Tensor], abits: int,
 
 def linear(Xq: torch.Tensor, scale: torch.Tensor, abits: int, Wq: torch.Tensor, wscale: torch.Tensor,
            M: int, N: int, K: int, Rp: Optional[torch.Tensor] = None, r: int = 0,
-           r_dtype: torch.dtype = torch.bfloat16, s_begin: int = 0,
+           r_dtype=torch.bfloat16, s_begin: int = 0,
            out_dtype: torch.dtype = torch.bfloat16, Y: Optional[torch.Tensor] = None,
            ws: Optional[torch.Tensor] = None, flags_: int = 0) -> torch.Tensor:
-    """serq_linear: Y = scale * (wscale * (Xq . Wq^T) + Xq[:, S] . R)."""
+    """serq_linear: Y = scale * (wscale * (Xq . Wq^T) + Xq[:, S] . R).  r_dtype is the 16-bit dtype of the
+    packed R, or the constant I4 when Rp is the blob of pack_lowrank_q4."""
     if Y is None:
         Y = torch.empty((M, N), dtype=out_dtype, device=Xq.device)
     rc = lib().serq_linear(_ptr(Xq), _ptr(scale), abits, _ptr(Wq), _ptr(wscale), s_begin, r, _ptr(Rp),
-                           _DT[r_dtype], M, N, K, _ptr(Y), _DT[Y.dtype], Y.stride(0),
+                           r_dtype if isinstance(r_dtype, int) else _DT[r_dtype], M, N, K, _ptr(Y), _DT[Y.dtype],
+                           Y.stride(0),
                            _ptr(ws), 0 if ws is None else ws.numel(), flags_, _stream())
     _check("serq_linear", rc)
     return Y

@@ -62,6 +62,11 @@ size_t serq_packed_lowrank_bytes(int64_t N, int r) {
   return (size_t)N * (size_t)r * 2;
 }
 
+size_t serq_packed_lowrank_q4_bytes(int64_t N, int r) {
+  if (N <= 0 || (N % 32) != 0 || N > (1 << 24) || r < 0 || (r % 16) != 0) return 0;
+  return lowrank_q4_frag_bytes((int)N, r) + (size_t)N * 4;
+}
+
 size_t serq_workspace_bytes(int64_t M, int64_t N, int64_t K, int r, int abits) {
   (void)r; (void)abits;
   if (check_nk(N, K) != SERQ_OK || M < 0) return 0;
@@ -118,6 +123,21 @@ int serq_unpack_lowrank(const void* Rp, int64_t N, int r, void* R_out, void* str
   if (N < 32 || (N % 32) != 0 || N > (1 << 24) || r < 0 || (r % 16) != 0) return SERQ_ESHAPE;
   if (!aligned16(Rp) || !aligned16(R_out)) return SERQ_EALIGN;
   return pack_lowrank_impl(R_out, (int)N, r, const_cast<void*>(Rp), true, (hipStream_t)stream);
+}
+
+int serq_pack_lowrank_q4(const void* R, int r_dtype, int64_t N, int r, void* Rq_out, void* stream) {
+  if (!R || !Rq_out) return SERQ_ENULL;
+  if (!dtype_ok(r_dtype)) return SERQ_EDTYPE;
+  if (N < 32 || (N % 32) != 0 || N > (1 << 24) || r < 0 || (r % 16) != 0) return SERQ_ESHAPE;
+  if (!aligned16(R) || !aligned16(Rq_out)) return SERQ_EALIGN;
+  return pack_lowrank_q4_impl(R, r_dtype, (int)N, r, Rq_out, (hipStream_t)stream);
+}
+
+int serq_unpack_lowrank_q4(const void* Rq, int64_t N, int r, int8_t* codes_out, float* rscale_out, void* stream) {
+  if (!Rq) return SERQ_ENULL;
+  if (N < 32 || (N % 32) != 0 || N > (1 << 24) || r < 0 || (r % 16) != 0) return SERQ_ESHAPE;
+  if (!aligned16(Rq) || (reinterpret_cast<uintptr_t>(rscale_out) & 3u)) return SERQ_EALIGN;
+  return unpack_lowrank_q4_impl(Rq, (int)N, r, codes_out, rscale_out, (hipStream_t)stream);
 }
 
 int serq_unpack_weights(const void* Wq, int64_t N, int64_t K, int8_t* out, void* stream) {
@@ -183,13 +203,15 @@ int serq_linear(const void* Xq, const float* scale, int abits,
   if (M > 0 && (!Y || !scale || !wscale)) return SERQ_ENULL;
   int rc = check_lowrank(K, s_begin, r);
   if (rc != SERQ_OK) return rc;
-  if (r > 0 && Rp && !dtype16(r_dtype)) return SERQ_EDTYPE;
+  if (r > 0 && Rp && !dtype16(r_dtype) && r_dtype != SERQ_I4) return SERQ_EDTYPE;
+  if (r > 0 && Rp && r_dtype == SERQ_I4 && (int64_t)s_begin + 64 * ((r + 63) / 64) > K) return SERQ_ESHAPE;
   if (ldy < N) return SERQ_ESHAPE;
   if ((ldy % 8) != 0 || !aligned16(Y) || (reinterpret_cast<uintptr_t>(scale) & 3u)) return SERQ_EALIGN;
   LinearArgs a{};
   a.Xq = (const uint8_t*)Xq; a.scale = scale; a.abits = abits;
   a.Wq = (const u4*)Wq; a.wscale = wscale;
   a.s_begin = s_begin; a.r = (Rp ? r : 0); a.Rp = (r > 0 ? (const u4*)Rp : nullptr); a.r_dtype = r_dtype;
+  a.rscale = (a.Rp && r_dtype == SERQ_I4) ? (const float*)((const char*)Rp + lowrank_q4_frag_bytes((int)N, r)) : nullptr;
   a.Y = Y; a.y_dtype = y_dtype; a.ldy = ldy;
   a.acc_out = nullptr; a.ldacc = 0;
   a.workspace = workspace; a.workspace_bytes = workspace_bytes;

@@ -69,7 +69,8 @@ struct Tile {
   static constexpr int LR_NLX = BM * LR_XROW / 16 / kThreads;
   static constexpr int NL_LR = 4 + LR_NLX;
   static constexpr int WS_OFF = NS * STAGE;           // 256 floats: the tile's weight scales
-  static constexpr int LDS_BYTES = WS_OFF + 256 * 4;
+  static constexpr int RS_OFF = WS_OFF + 256 * 4;     // 256 floats: the scales of a 4-bit compensation matrix
+  static constexpr int LDS_BYTES = RS_OFF + 256 * 4;
   static_assert(LR_R_BYTES + BM * LR_XROW <= STAGE, "a low-rank tile fits a stage");
   static_assert(NS == 2 || NL == NL_LR, "one vmcnt immediate serves both tile kinds");
   static_assert(BM * 512 <= NS * STAGE, "the 16-bit output tile fits the ring");
@@ -80,6 +81,7 @@ struct MfmaParams {
   const uint8_t* Xq; const float* scale;
   const u4* Wq; const float* wscale;
   const u4* Rp; int r_dtype; int s_begin; int r;
+  const float* rscale;    // r_dtype == SERQ_I4: per-channel scales of the 4-bit compensation matrix
   int M, N, K;
   void* Y; int y_dtype; int64_t ldy;
   int32_t* acc_out; int64_t ldacc;
@@ -141,7 +143,8 @@ __device__ __forceinline__ v4i widen(uint32_t d0, uint32_t d1) {
   return v4i{a, b, c, d};
 }
 
-template <int ABITS>
+// LRQ: the compensation matrix is the 4-bit blob (its tiles run on the int8 units) instead of 16-bit fragments
+template <int ABITS, bool LRQ>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void serq_mfma_kernel(const MfmaParams p) {
   using T = Tile<ABITS>;
@@ -172,13 +175,16 @@ void serq_mfma_kernel(const MfmaParams p) {
   const int KTAIL = KB - KTF * CH;                   // fragments of a last, partial main tile
   const int KT = KTF + (KTAIL ? 1 : 0);
   const int JB = (p.acc_out == nullptr) ? (p.r >> 4) : 0;
-  const int LT = (JB + 3) >> 2;                      // low-rank tiles of up to 4 x 16 channels
+  const int LT = (JB + 3) >> 2;                      // low-rank tiles of 64 salient channels (16-bit R: up to 4 x 16)
+  constexpr bool lr_int = LRQ;                       // one weight-like fragment per tile and block
   const int TT = KT + LT;
 
   // the tile's weight scales, times 2^-SH (exact), for the int -> float conversion
   constexpr float kInv = 1.0f / (float)(1 << T::SH);
   float* lws = reinterpret_cast<float*>(lds + T::WS_OFF);
   if (tid < 256 && p.wscale != nullptr) lws[tid] = tid < 32 * nbt ? p.wscale[n0 + tid] * kInv : 0.0f;
+  float* lrs = reinterpret_cast<float*>(lds + T::RS_OFF);
+  if (tid < 256 && lr_int && LT > 0) lrs[tid] = tid < 32 * nbt ? p.rscale[n0 + tid] * kInv : 0.0f;
 
   const int wu = __builtin_amdgcn_readfirstlane(w);
   const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_addr(lds));
@@ -238,15 +244,24 @@ void serq_mfma_kernel(const MfmaParams p) {
   // low-rank tile lt (4 x 16 salient channels) into stage st
   auto issue_lr = [&](int lt, int st) {
     const uint32_t sb = lds0 + (uint32_t)st * STAGE + (uint32_t)wu * 1024;
-    const int njb = JB - 4 * lt < 4 ? JB - 4 * lt : 4;
-    const uint8_t* rbase = (const uint8_t*)p.Rp + ((size_t)nb0 * JB + 4 * lt) * 1024;
+    if constexpr (lr_int) {
+      // wave w brings the fragment of block w to slot w; the other three loads of a wave repeat it
+      // into unused slots so that every tile kind issues the same number of loads
+      const uint8_t* rbase = (const uint8_t*)p.Rp + ((size_t)nb0 * LT + lt) * 1024;
+      const int nbl = wu < nbt ? wu : nbt - 1;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int f = i * kWaves + wu;                 // f = nbl*4 + jbl
-      int nbl = f >> 2, jbl = f & 3;
-      nbl = nbl < nbt ? nbl : nbt - 1;
-      jbl = jbl < njb ? jbl : 0;
-      dma16(rbase, (uint32_t)((nbl * JB + jbl) * 1024 + l * 16), sb + kWaves * 1024 * i);
+      for (int i = 0; i < 4; ++i) dma16(rbase, (uint32_t)(nbl * LT * 1024 + l * 16), sb + kWaves * 1024 * i);
+    } else {
+      const int njb = JB - 4 * lt < 4 ? JB - 4 * lt : 4;
+      const uint8_t* rbase = (const uint8_t*)p.Rp + ((size_t)nb0 * JB + 4 * lt) * 1024;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int f = i * kWaves + wu;               // f = nbl*4 + jbl
+        int nbl = f >> 2, jbl = f & 3;
+        nbl = nbl < nbt ? nbl : nbt - 1;
+        jbl = jbl < njb ? jbl : 0;
+        dma16(rbase, (uint32_t)((nbl * JB + jbl) * 1024 + l * 16), sb + kWaves * 1024 * i);
+      }
     }
     if constexpr (ABITS == 8) {
       const uint8_t* cbase = xbase + p.s_begin + 64 * lt;
@@ -512,16 +527,67 @@ void serq_mfma_kernel(const MfmaParams p) {
         }
       }
     };
+    // A tile of a 4-bit compensation matrix: per channel block one weight-like fragment of 64 ranks,
+    // multiplied on the int8 units against the tile's token codes into a scratch INT32 tile that is
+    // scaled by rscale[n] * 2^-SH and added to the fp32 accumulators.
+    auto lr_tile_int = [&](const uint8_t* stp) {
+      // the scales are the same for every tile; an opaque offset keeps the compiler from holding all
+      // 64 of them in registers across the tiles
+      int rs_off = 0;
+      asm volatile("" : "+v"(rs_off));
+      const float* lrs_t = lrs + rs_off;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        v4i xb0, xb1;
+        if constexpr (ABITS == 8) {
+          xb0 = *(const v4i*)(stp + lr_x_off[j] + 16 * ((2 * g) ^ lr_x_swz[j]));
+          xb1 = *(const v4i*)(stp + lr_x_off[j] + 16 * ((2 * g + 1) ^ lr_x_swz[j]));
+        } else {
+          const u4 xp = *(const u4*)(stp + lr_x_off[j] + 16 * (g ^ lr_x_swz[j]));
+          xb0 = widen(xp.x, xp.y);
+          xb1 = widen(xp.z, xp.w);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          if (i < NBW) {
+            const u4 rq = *(const u4*)(stp + (blk0 + i) * 1024 + l * 16);
+            v16i tq;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) tq[e] = 0;
+            tq = __builtin_amdgcn_mfma_i32_32x32x32_i8(widen(rq.x, rq.y), xb0, tq, 0, 0, 0);
+            tq = __builtin_amdgcn_mfma_i32_32x32x32_i8(widen(rq.z, rq.w), xb1, tq, 0, 0, 0);
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+              const int cl = 32 * (blk0 + i) + 8 * q4 + 4 * g;
+              const float4 rs = *(const float4*)(lrs_t + (cl < 256 ? cl : 0));
+              const float r4[4] = {rs.x, rs.y, rs.z, rs.w};
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                accf[i][j][4 * q4 + e] = __builtin_fmaf(r4[e], (float)tq[4 * q4 + e], accf[i][j][4 * q4 + e]);
+            }
+          }
+          // pin the update here: left alone, the compiler sinks it below the hand-off and keeps
+          // four scratch tiles and all their scales alive until then
+          if (i < NBW) asm volatile("" : "+v"(accf[i][j]));
+          fence();
+        }
+      }
+    };
     // low-rank tiles; during them every refill is another low-rank tile
     fence();
     for (int lt = 0; lt < LT; ++lt) {
-      const int njb = (JB - 4 * lt) < 4 ? (JB - 4 * lt) : 4;
-      for (int jb4 = 0; jb4 < njb; ++jb4) {
-        LrFrag G;
-        load_lr_frags(stage_ptr(st), jb4, G);
+      if constexpr (lr_int) {
+        lr_tile_int(stage_ptr(st));
         fence();
-        mfma_lr(G);
-        fence();
+      } else {
+        const int njb = (JB - 4 * lt) < 4 ? (JB - 4 * lt) : 4;
+        for (int jb4 = 0; jb4 < njb; ++jb4) {
+          LrFrag G;
+          load_lr_frags(stage_ptr(st), jb4, G);
+          fence();
+          mfma_lr(G);
+          fence();
+        }
       }
       handoff_wait();
       if (t + NS < TT) issue_lr(t + NS - KT, st);
@@ -634,6 +700,7 @@ int launch_mfma(const LinearArgs& a, hipStream_t st) {
   MfmaParams p;
   p.Xq = a.Xq; p.scale = a.scale; p.Wq = a.Wq; p.wscale = a.wscale;
   p.Rp = a.Rp; p.r_dtype = a.r_dtype; p.s_begin = a.s_begin; p.r = a.Rp ? a.r : 0;
+  p.rscale = a.rscale;
   p.M = a.M; p.N = a.N; p.K = a.K;
   p.Y = a.Y; p.y_dtype = a.y_dtype; p.ldy = a.ldy;
   p.acc_out = a.acc_out; p.ldacc = a.ldacc;
@@ -650,8 +717,14 @@ int launch_mfma(const LinearArgs& a, hipStream_t st) {
   const long long tiles = (long long)p.tiles_m * p.tiles_n;
   if (tiles > 0x7fffffffLL) return SERQ_ESHAPE;
   dim3 grid((unsigned)tiles), block(kThreads);
-  if (a.abits == 8) hipLaunchKernelGGL(serq_mfma_kernel<8>, grid, block, 0, st, p);
-  else hipLaunchKernelGGL(serq_mfma_kernel<4>, grid, block, 0, st, p);
+  const bool lrq = p.r > 0 && p.r_dtype == SERQ_I4 && p.acc_out == nullptr;
+  if (a.abits == 8) {
+    if (lrq) hipLaunchKernelGGL((serq_mfma_kernel<8, true>), grid, block, 0, st, p);
+    else hipLaunchKernelGGL((serq_mfma_kernel<8, false>), grid, block, 0, st, p);
+  } else {
+    if (lrq) hipLaunchKernelGGL((serq_mfma_kernel<4, true>), grid, block, 0, st, p);
+    else hipLaunchKernelGGL((serq_mfma_kernel<4, false>), grid, block, 0, st, p);
+  }
   return hipGetLastError() == hipSuccess ? SERQ_OK : SERQ_EHIP;
 }
 

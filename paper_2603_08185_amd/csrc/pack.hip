@@ -165,6 +165,65 @@ __global__ __launch_bounds__(kT) void pack_lowrank_kernel(uint16_t* __restrict__
   else Rp[pidx] = R[idx];
 }
 
+// ---- the 4-bit compensation matrix Q(R) (Eq. 7, second line) -------------------
+// Blob: [N/32][ceil(r/64)] fragments of 1 KiB in the weight-fragment layout with the rank index j in
+// the place of the input channel (ranks past r hold zero codes), then rscale [N] fp32.
+
+// rscale[n] = max_j |R[j,n]| / 7   (Eq. 1 per output channel; 1.0 for a zero column)
+__global__ __launch_bounds__(kT) void lowrank_scale_kernel(const void* __restrict__ R, int r_dtype, int N, int r,
+                                                           float* __restrict__ rscale) {
+  const int n = blockIdx.x * kT + threadIdx.x;
+  if (n >= N) return;
+  float m = 0.0f;
+  for (int j = 0; j < r; ++j) m = fmaxf(m, fabsf(ld_any(R, r_dtype, (size_t)j * N + n)));
+  rscale[n] = m > 0.0f ? m / 7.0f : 1.0f;
+}
+
+// one thread per packed dword
+__global__ __launch_bounds__(kT) void lowrank_q4_pack_kernel(const void* __restrict__ R, int r_dtype, int N, int r,
+                                                             const float* __restrict__ rscale,
+                                                             uint32_t* __restrict__ blob) {
+  const int FR = (r + 63) >> 6;
+  const size_t idx = (size_t)blockIdx.x * kT + threadIdx.x;
+  if (idx >= (size_t)(N / 32) * FR * 256) return;
+  const int d = idx & 3;
+  const int lane = (idx >> 2) & 63;
+  const size_t frag = idx >> 8;
+  const int fb = frag % FR;
+  const size_t n = (frag / FR) * 32 + (lane & 31);
+  const int j0 = fb * 64 + (lane >> 5) * 32 + d * 8;
+  const float rs = rscale[n];
+  auto code = [&](int j) {
+    if (j >= r) return 0;
+    float t = rintf(ld_any(R, r_dtype, (size_t)j * N + n) / rs);
+    return (int)fminf(fmaxf(t, -7.0f), 7.0f);
+  };
+  uint32_t out = 0;
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj)
+    out |= ((uint32_t)(code(j0 + jj) & 0xf) | ((uint32_t)(code(j0 + 4 + jj) & 0xf) << 4)) << (8 * jj);
+  blob[idx] = out;
+}
+
+// canonical view: codes int8 [r,N]; one thread per packed dword
+__global__ __launch_bounds__(kT) void lowrank_q4_unpack_kernel(const uint32_t* __restrict__ blob, int N, int r,
+                                                               int8_t* __restrict__ out) {
+  const int FR = (r + 63) >> 6;
+  const size_t idx = (size_t)blockIdx.x * kT + threadIdx.x;
+  if (idx >= (size_t)(N / 32) * FR * 256) return;
+  const int d = idx & 3;
+  const int lane = (idx >> 2) & 63;
+  const size_t frag = idx >> 8;
+  const int fb = frag % FR;
+  const size_t n = (frag / FR) * 32 + (lane & 31);
+  const int j0 = fb * 64 + (lane >> 5) * 32 + d * 8;
+  int c[8];
+  codes_from_a4(blob[idx], c);
+#pragma unroll
+  for (int jj = 0; jj < 8; ++jj)
+    if (j0 + jj < r) out[(size_t)(j0 + jj) * N + n] = (int8_t)c[jj];
+}
+
 __global__ __launch_bounds__(kT) void unpack_weights_kernel(const uint32_t* __restrict__ blob, int N, int K,
                                                             int8_t* __restrict__ out) {
   const size_t idx = (size_t)blockIdx.x * kT + threadIdx.x;
@@ -226,6 +285,30 @@ int pack_lowrank_impl(void* R, int N, int r, void* Rp, bool unpack, hipStream_t 
   if (r == 0) return SERQ_OK;
   hipLaunchKernelGGL(pack_lowrank_kernel, dim3(blocks_for((size_t)r * N)), dim3(kT), 0, st, (uint16_t*)R, N, r,
                      (uint16_t*)Rp, unpack);
+  return ok();
+}
+
+size_t lowrank_q4_frag_bytes(int N, int r) { return (size_t)(N / 32) * ((r + 63) / 64) * 1024; }
+
+int pack_lowrank_q4_impl(const void* R, int r_dtype, int N, int r, void* Rq, hipStream_t st) {
+  if (r == 0) return SERQ_OK;
+  const size_t fb = lowrank_q4_frag_bytes(N, r);
+  float* rscale = (float*)((char*)Rq + fb);
+  hipLaunchKernelGGL(lowrank_scale_kernel, dim3(blocks_for(N)), dim3(kT), 0, st, R, r_dtype, N, r, rscale);
+  hipLaunchKernelGGL(lowrank_q4_pack_kernel, dim3(blocks_for(fb / 4)), dim3(kT), 0, st, R, r_dtype, N, r, rscale,
+                     (uint32_t*)Rq);
+  return ok();
+}
+
+int unpack_lowrank_q4_impl(const void* Rq, int N, int r, int8_t* codes, float* rscale, hipStream_t st) {
+  if (r == 0) return SERQ_OK;
+  const size_t fb = lowrank_q4_frag_bytes(N, r);
+  if (codes)
+    hipLaunchKernelGGL(lowrank_q4_unpack_kernel, dim3(blocks_for(fb / 4)), dim3(kT), 0, st, (const uint32_t*)Rq, N, r,
+                       codes);
+  if (rscale &&
+      hipMemcpyAsync(rscale, (const char*)Rq + fb, (size_t)N * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
+    return SERQ_EHIP;
   return ok();
 }
 

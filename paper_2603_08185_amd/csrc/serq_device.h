@@ -154,6 +154,7 @@ struct LinearArgs {
   const uint8_t* Xq; const float* scale; int abits;
   const u4* Wq; const float* wscale;
   int s_begin; int r; const u4* Rp; int r_dtype;
+  const float* rscale;                  // r_dtype == SERQ_I4: the per-channel scales inside the blob Rp
   int M, N, K;
   void* Y; int y_dtype; int64_t ldy;
   int32_t* acc_out; int64_t ldacc;      // non-NULL: store raw accumulators instead of Y
@@ -172,6 +173,9 @@ int pack_weights_impl(const void* W, int w_dtype, const float* s, const int32_t*
                       void* Wq_out, float* wscale_out, int32_t* perm_out, float* s_inv_out, void* R_out,
                       int r_dtype, void* Rp_out, hipStream_t st);
 int pack_lowrank_impl(void* R, int N, int r, void* Rp, bool unpack, hipStream_t st);
+size_t lowrank_q4_frag_bytes(int N, int r);
+int pack_lowrank_q4_impl(const void* R, int r_dtype, int N, int r, void* Rq, hipStream_t st);
+int unpack_lowrank_q4_impl(const void* Rq, int N, int r, int8_t* codes, float* rscale, hipStream_t st);
 int unpack_weights_impl(const void* Wq, int N, int K, int8_t* out, hipStream_t st);
 int unpack_act_impl(const void* Xq, int abits, int64_t M, int K, int8_t* out, hipStream_t st);
 

@@ -52,7 +52,9 @@ struct SkinnyParams {
   int32_t* acc_out; int64_t ldacc;
   int splitk;
   int region;                           // bytes of LDS per wave
-  int32_t* part_i; float* part_f;       // [N/32][splitk][1024] each
+  int lrx_off;                          // where in its region a wave keeps the token codes of a 4-bit R fragment
+  const float* rscale;                  // scales of a 4-bit compensation matrix (r_dtype == SERQ_I4)
+  int32_t* part_i; int32_t* part_l;     // [N/32][splitk][1024] INT32 sums; [N/32][1024] rank-r sums (fp32 bits or INT32)
 };
 
 // y for (token m, channel n) from the two sums; one store
@@ -95,7 +97,7 @@ struct Stage {
 };
 
 template <int ABITS, int kWaves, int kGroup>
-__global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGroup == 8 ? 4 : 5, 8))) void serq_skinny_kernel(
+__global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu((kGroup == 8 || kWaves == 4) ? 4 : 5, 8))) void serq_skinny_kernel(
     // needed before the first load is issued: passed one by one so that the dispatcher can preload them into SGPRs
     const uint8_t* hXq, const u4* hWq, int hK, int hM, int kb_per, int kb_rem, int hregion,
     const SkinnyParams p) {
@@ -117,17 +119,19 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGr
   const uint8_t* xrow = hXq + (size_t)(mv ? m : 0) * rowbytes;
   const u4* wfr = hWq + (size_t)nb * KB * 64 + l;
   uint8_t* my = lds + (size_t)w * hregion;
+  const uint32_t my_lds = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_addr(my));
 
   v16i acc;
 #pragma unroll
   for (int e = 0; e < 16; ++e) acc[e] = 0;
 
   // ---- cache-resident operands of the epilogue, requested first ---------------
-  // the token codes of the rank-r term (blocks of 16 salient channels, slice 0 only; one block per wave
-  // is requested up front) ...
+  // the token codes of the rank-r term (slice 0 only; one fragment of R per wave is requested up front):
+  // blocks of 16 salient channels for a 16-bit R, of 64 for a 4-bit one ...
   const bool has_lr = p.r > 0 && p.acc_out == nullptr;
   const bool lr_here = has_lr && ks == 0;
-  const int JB = p.r >> 4;
+  const bool lr_int = p.r_dtype == SERQ_I4;
+  const int JB = lr_int ? (p.r + 63) >> 6 : p.r >> 4;  // fragments of R per channel block
   const bool bf = p.r_dtype == SERQ_BF16;
   const u4* rfr = p.Rp + (size_t)nb * JB * 64 + l;
   auto lr_load_x = [&](int jb) {
@@ -139,19 +143,30 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGr
     }
     return x;
   };
+  // 4-bit R: this lane's 32 (16) bytes of codes for fragment jf go straight to its own LDS slot
+  auto lr_dma_x = [&](int jf) {
+    const uint32_t off = (uint32_t)(mv ? m : 0) * (uint32_t)rowbytes +
+                         (uint32_t)((p.s_begin + 64 * jf) * ABITS / 8 + g * (S::FB / 2));
+    dma16(hXq, off, my_lds + (uint32_t)p.lrx_off);
+    if constexpr (ABITS == 8) dma16(hXq, off + 16, my_lds + (uint32_t)p.lrx_off + 1024u);
+  };
   const bool lr_first = lr_here && w < JB;
   u2 xc = {0u, 0u};
-  if (lr_first) xc = lr_load_x(w);
+  if (lr_first) {
+    if (lr_int) lr_dma_x(w);
+    else xc = lr_load_x(w);
+  }
   // ... and the scales of the outputs this thread will finish
   constexpr int NQ = 1024 / kThreads;
-  float sc_m[NQ], sc_n[NQ];
+  float sc_m[NQ], sc_n[NQ], sc_r[NQ];
 #pragma unroll
   for (int q = 0; q < NQ; ++q) {
     const int id = tid + q * kThreads;
-    sc_m[q] = sc_n[q] = 0.0f;
+    sc_m[q] = sc_n[q] = sc_r[q] = 0.0f;
     if (p.acc_out == nullptr && gridDim.y == 1 && (id >> 5) < hM) {
       sc_m[q] = p.scale[id >> 5];
       sc_n[q] = p.wscale[nb * 32 + (id & 31)];
+      if (has_lr && lr_int) sc_r[q] = p.rscale[nb * 32 + (id & 31)];
     }
   }
   u4 rf = {0u, 0u, 0u, 0u};
@@ -162,7 +177,6 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGr
   const int srow0 = l / S::P, slot = l % S::P;
   const int nfr = kb1 - kb0;                            // fragments in the slice
   const uint8_t* xslice = hXq + (size_t)kb0 * S::FB;
-  const uint32_t my_lds = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_addr(my));
 #pragma unroll 1
   for (int gi = w; gi * kGroup < nfr; gi += kWaves) {
     const int f0 = gi * kGroup;                         // first fragment of the group, relative to the slice
@@ -208,23 +222,52 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGr
   }
 
   // ---- the rank-r term ----------------------------------------------------------
-  v16f accf;
+  // its sums: fp32 bit patterns for a 16-bit R, INT32 (times 2^SH like the main sums) for a 4-bit one
+  v16i accl;
 #pragma unroll
-  for (int e = 0; e < 16; ++e) accf[e] = 0.0f;
+  for (int e = 0; e < 16; ++e) accl[e] = 0;
   auto lr_mfma = [&](const u4& r_in, const u2& x_in) {
     int c[8];
     if constexpr (ABITS == 8) codes_from_a8(x_in.x, x_in.y, c);
     else codes_from_a4(x_in.x, c);
     u4 xf = codes8_to_16bit(c, bf);                     // zero codes for lanes without a token
+    v16f af = __builtin_bit_cast(v16f, accl);
     if (bf)
-      accf = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, r_in), __builtin_bit_cast(v8bf, xf),
-                                                     accf, 0, 0, 0);
+      af = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, r_in), __builtin_bit_cast(v8bf, xf), af, 0, 0, 0);
     else
-      accf = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, r_in), __builtin_bit_cast(v8h, xf),
-                                                    accf, 0, 0, 0);
+      af = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, r_in), __builtin_bit_cast(v8h, xf), af, 0, 0, 0);
+    accl = __builtin_bit_cast(v16i, af);
   };
-  if (lr_first) lr_mfma(rf, xc);
-  if (lr_here) {
+  auto lr_mfma_int = [&](const u4& r_in) {              // one 64-rank fragment of Q(R) against the parked codes
+    v4i a0, a1, b0, b1;
+    unpack_frag(r_in, a0, a1);
+    b0 = (v4i){0, 0, 0, 0};
+    b1 = (v4i){0, 0, 0, 0};
+    if (mv) {
+      const uint8_t* xp = my + p.lrx_off + l * 16;
+      if constexpr (ABITS == 8) {
+        b0 = *(const v4i*)xp;
+        b1 = *(const v4i*)(xp + 1024);
+      } else {
+        unpack_frag(*(const u4*)xp, b0, b1);
+      }
+    }
+    accl = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, accl, 0, 0, 0);
+    accl = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, accl, 0, 0, 0);
+  };
+  if (lr_here && lr_int) {
+    if (lr_first) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the parked codes (a wave without a group never waited)
+      lr_mfma_int(rf);
+    }
+    for (int jf = w + kWaves; jf < JB; jf += kWaves) {  // fragments beyond the first of each wave
+      lr_dma_x(jf);
+      const u4 r1 = __builtin_nontemporal_load(&rfr[(size_t)jf * 64]);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      lr_mfma_int(r1);
+    }
+  } else if (lr_here) {
+    if (lr_first) lr_mfma(rf, xc);
     for (int jb = w + kWaves; jb < JB; jb += kWaves) {  // ranks beyond the first block of each wave
       const u4 r1 = __builtin_nontemporal_load(&rfr[(size_t)jb * 64]);
       lr_mfma(r1, lr_load_x(jb));
@@ -237,7 +280,7 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGr
   // partials in its own region (dead as token staging by now) as [token][channel]
   // rows of kRedPitch words -- four 16-byte writes per lane, and a pitch of 9
   // bank groups keeps both the writes and the gather conflict-free -- with the
-  // fp32 partials M rows further.
+  // rank-r partials M rows further.
   // Thread tid finishes (token q/32, channel q%32) for q = tid, tid + kThreads, ...
   const int nwl = JB < kWaves ? JB : kWaves;              // waves that hold low-rank sums
   if (mv) {
@@ -246,10 +289,10 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGr
     for (int i = 0; i < 4; ++i)
       *reinterpret_cast<v4i*>(red + 8 * i) = (v4i){acc[4 * i], acc[4 * i + 1], acc[4 * i + 2], acc[4 * i + 3]};
     if (lr_here && w < nwl) {
-      float* redf = reinterpret_cast<float*>(red + hM * kRedPitch);
+      int* redl = red + hM * kRedPitch;
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        *reinterpret_cast<v4f*>(redf + 8 * i) = (v4f){accf[4 * i], accf[4 * i + 1], accf[4 * i + 2], accf[4 * i + 3]};
+        *reinterpret_cast<v4i*>(redl + 8 * i) = (v4i){accl[4 * i], accl[4 * i + 1], accl[4 * i + 2], accl[4 * i + 3]};
     }
   }
   __syncthreads();
@@ -259,18 +302,23 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(kGr
     const int nl = id & 31, mt = id >> 5;
     if (mt >= hM) continue;
     const int src = mt * kRedPitch + nl;
-    int tot_i = 0;
+    int tot_i = 0, tot_li = 0;
     float tot_f = 0.0f;
 #pragma unroll
     for (int ww = 0; ww < kWaves; ++ww) tot_i += *reinterpret_cast<const int*>(lds + (size_t)ww * hregion + 4 * src);
     if (lr_here)
-      for (int ww = 0; ww < nwl; ++ww) tot_f += *reinterpret_cast<const float*>(lds + (size_t)ww * hregion + 4 * (hM * kRedPitch + src));
+      for (int ww = 0; ww < nwl; ++ww) {
+        const int word = *reinterpret_cast<const int*>(lds + (size_t)ww * hregion + 4 * (hM * kRedPitch + src));
+        if (lr_int) tot_li += word;
+        else tot_f += __int_as_float(word);
+      }
     if (p.splitk > 1) {
       // partial sums of this slice; the reduce kernel finishes the job
       p.part_i[((size_t)nb * p.splitk + ks) * 1024 + id] = tot_i;
-      if (lr_here) p.part_f[(size_t)nb * 1024 + id] = tot_f;
+      if (lr_here) p.part_l[(size_t)nb * 1024 + id] = lr_int ? tot_li : __float_as_int(tot_f);
     } else {
-      finish(p, mt, nb * 32 + nl, tot_i >> SH, tot_f, sc_m[q], sc_n[q]);   // exact shift: the sum is a multiple of 2^SH
+      const float lr = lr_int ? sc_r[q] * (float)(tot_li >> SH) : tot_f;
+      finish(p, mt, nb * 32 + nl, tot_i >> SH, lr, sc_m[q], sc_n[q]);   // exact shifts: the sums are multiples of 2^SH
     }
   }
 }
@@ -286,8 +334,12 @@ __global__ __launch_bounds__(1024) void serq_skinny_reduce_kernel(const SkinnyPa
   int tot_i = 0;
   for (int s = 0; s < p.splitk; ++s) tot_i += p.part_i[((size_t)nb * p.splitk + s) * 1024 + tid];
   const bool has_lr = p.r > 0 && p.acc_out == nullptr;
-  const float tot_f = has_lr ? p.part_f[(size_t)nb * 1024 + tid] : 0.0f;
   const int n = nb * 32 + (tid & 31);
+  float tot_f = 0.0f;
+  if (has_lr) {
+    const int word = p.part_l[(size_t)nb * 1024 + tid];
+    tot_f = p.r_dtype == SERQ_I4 ? p.rscale[n] * (float)(word >> SH) : __int_as_float(word);
+  }
   const bool scaled = p.acc_out == nullptr;
   finish(p, mt, n, tot_i >> SH, tot_f, scaled ? p.scale[mt] : 0.0f, scaled ? p.wscale[n] : 0.0f);
 }
@@ -331,7 +383,8 @@ int launch_skinny(const LinearArgs& a, hipStream_t st) {
   }
   p.splitk = splitk;
   p.part_i = splitk > 1 ? (int32_t*)a.workspace : nullptr;
-  p.part_f = splitk > 1 ? (float*)((char*)a.workspace + nblk * (size_t)splitk * 1024 * 4) : nullptr;
+  p.part_l = splitk > 1 ? (int32_t*)((char*)a.workspace + nblk * (size_t)splitk * 1024 * 4) : nullptr;
+  p.rscale = a.rscale;
 
   // Waves per workgroup: 8 once the slice gives each of them a group of fragments, else 4.  (16-wave
   // workgroups measured slower: their registers and LDS allow one workgroup per CU where two or three
@@ -351,6 +404,8 @@ int launch_skinny(const LinearArgs& a, hipStream_t st) {
   const int rows = (a.M + rpi - 1) / rpi * rpi;
   const bool has_lr = p.r > 0 && p.acc_out == nullptr;
   int region = rows * rowb;
+  p.lrx_off = region;
+  if (has_lr && a.r_dtype == SERQ_I4) region += a.abits == 8 ? 2048 : 1024;
   const int red = (has_lr ? 2 : 1) * a.M * kRedPitch * 4;
   if (red > region) region = red;
   region = (region + 15) & ~15;

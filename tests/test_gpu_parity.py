@@ -322,6 +322,93 @@ def test_salient_block_offset_and_rank_zero():
         assert torch.equal(Y0, Yn)
 
 
+# ---------------------------------------------------------------------------
+# the 4-bit compensation matrix Q(R) (Eq. 7, second line)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("N,r", [(32, 16), (96, 48), (288, 64), (1024, 128), (64, 208)])
+def test_pack_lowrank_q4_matches_oracle(dtype, N, r):
+    g = torch.Generator().manual_seed(N + r)
+    R = (torch.randn((r, N), generator=g) * 0.01).to(dtype)
+    R[:, 5] = 0                                        # a zero column: scale 1, codes 0
+    R[3, 7] = R[:, 7].abs().max() * 2                  # and a column whose extreme is unique
+    Rq, rscale = orc.quantize_lowrank(R.float().numpy())
+    blob = serq.pack_lowrank_q4(R.to(DEV))
+    codes, rs = serq.unpack_lowrank_q4(blob, N, r)
+    assert np.array_equal(rs.cpu().numpy().view(np.uint32), rscale.view(np.uint32))
+    assert np.array_equal(codes.cpu().numpy(), Rq)
+
+
+def _run_layer_q4r(spec, path=serq.PATH_AUTO, splitk=0, groupm=0, rows=None, s_begin=0):
+    L = workloads.make_layer(spec)
+    O = oracle_layer(spec, L, rows=rows)
+    pk = serq.pack_weights(L["W"].to(DEV), L["s"].to(DEV), 0, want_R=False, want_Rp=False)
+    Xq, scale = serq.quantize_act(O.Xhat.to(DEV), pk.s_inv, spec.abits)
+    Rq, rscale = orc.quantize_lowrank(L["R"].float().numpy())
+    blob = serq.pack_lowrank_q4(L["R"].to(DEV))
+    ws = serq.workspace(spec.M, spec.N, spec.K, spec.r, spec.abits, DEV)
+    Y = serq.linear(Xq, scale, spec.abits, pk.Wq, pk.wscale, spec.M, spec.N, spec.K, Rp=blob, r=spec.r,
+                    r_dtype=serq.I4, s_begin=s_begin, out_dtype=DT[spec.out_dtype], ws=ws,
+                    flags_=serq.flags(path, splitk=splitk, groupm=groupm))
+    Y64 = orc.linear_q4r(O.Xq, O.scale, O.pk["Wq"], O.pk["wscale"], Rq, rscale, s_begin=s_begin)
+    Ysel = Y if rows is None else Y[torch.as_tensor(O.rows, device=Y.device)]
+    return assert_y_close(Ysel, Y64, spec.name + " q4r")
+
+
+@pytest.mark.parametrize("abits", [4, 8])
+@pytest.mark.parametrize("out_dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("M,K,N,r,path", [
+    (3, 192, 96, 16, serq.PATH_SKINNY),
+    (32, 1088, 288, 128, serq.PATH_SKINNY),
+    (1, 4096, 64, 256, serq.PATH_SKINNY),
+    (5, 1024, 64, 144, serq.PATH_SKINNY),
+    (40, 192, 96, 32, serq.PATH_MFMA),
+    (300, 1088, 288, 128, serq.PATH_MFMA),
+    (257, 512, 544, 64, serq.PATH_MFMA),
+    (70, 320, 64, 48, serq.PATH_MFMA),
+    (130, 256, 96, 80, serq.PATH_MFMA),
+    (64, 832, 32, 16, serq.PATH_MFMA),
+    (513, 640, 800, 256, serq.PATH_MFMA),
+])
+def test_layer_q4r_small_shapes(abits, out_dtype, M, K, N, r, path):
+    spec = _small_spec(abits, M, K, N, r, out_dtype=out_dtype)
+    _run_layer_q4r(spec, path=path)
+    if path == serq.PATH_SKINNY:
+        _run_layer_q4r(spec, path=path, splitk=2)
+        _run_layer_q4r(spec, path=path, groupm=1)
+
+
+@pytest.mark.parametrize("path", [serq.PATH_SKINNY, serq.PATH_MFMA])
+def test_layer_q4r_salient_block_offset(path):
+    spec = _small_spec(8, 9, 512, 64, 80)
+    _run_layer_q4r(spec, path=path, s_begin=96)
+
+
+@pytest.mark.parametrize("which,M", [("up", 1), ("up", 16), ("down", 1), ("down", 256)])
+def test_config3_q4r(which, M):
+    _run_layer_q4r(workloads.config3(which, M))
+
+
+def test_config3_q4r_M4096_sampled_rows():
+    rows = np.sort(np.random.default_rng(43).choice(4096, size=64, replace=False))
+    rows[0], rows[-1] = 0, 4095
+    _run_layer_q4r(workloads.config3("up", 4096), rows=rows)
+
+
+@pytest.mark.parametrize("M", [1, 32])
+def test_config4_q4r(M):
+    _run_layer_q4r(workloads.config4(M))
+
+
+def test_q4r_error_codes():
+    x = torch.zeros(64 * 64, dtype=torch.uint8, device=DEV)
+    sc = torch.ones(64, dtype=torch.float32, device=DEV)
+    y = torch.empty((1, 64), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(serq.SerqError) as e:           # the 64-rank fragment would read past K
+        serq.linear(x, sc, 8, x, sc, 1, 64, 64, Rp=x, r=16, r_dtype=serq.I4, s_begin=32, Y=y)
+    assert e.value.code == -3
+
+
 def test_config2_attention_projection():
     _run_layer(workloads.config2())
 
