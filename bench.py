@@ -343,7 +343,7 @@ def main():
         "config": {"workload": "configs[2]: MLP up projection W4A8, M=4096, K=4096->N=11008, r=128, bf16 in/out; "
                                "step = serq_quantize_act + serq_linear",
                    "M": spec.M, "K": spec.K, "N": spec.N, "r": spec.r, "abits": spec.abits},
-        "roofline": {"bound": "mfma", "kernel": "serq_mfma_kernel<8> (serq_linear)",
+        "roofline": {"bound": "mfma", "kernel": "serq_mfma_kernel<8, 2> (serq_linear; W4A8, bf16 R)",
                      "achieved": round(pre["tops_linear"], 2), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
                      "frac": round(pre["tops_linear"] / INT8_PEAK_TOPS, 4), "traffic": LINEAR_TRAFFIC_BYTES,
                      "kernel_ms": round(pre["linear_ms"], 5)},

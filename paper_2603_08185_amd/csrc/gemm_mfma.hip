@@ -131,10 +131,6 @@ struct Frag {                       // one 64-channel fragment of a main tile
   u4 w[4];                          // packed weights of the wave's channel blocks
   u4 x[ABITS == 8 ? 4 : 2];         // tokens: 8-bit: [2*j + half], 4-bit: [j] (packed)
 };
-struct LrFrag {                     // 16 salient channels of a low-rank tile
-  u4 r[4];                          // R fragments of the wave's channel blocks
-  u2 x[2];                          // codes of the 2 token blocks (4-bit: .x only)
-};
 
 __device__ __forceinline__ v4i widen(uint32_t d0, uint32_t d1) {
   int a, b, c, d;
@@ -143,8 +139,11 @@ __device__ __forceinline__ v4i widen(uint32_t d0, uint32_t d1) {
   return v4i{a, b, c, d};
 }
 
-// LRQ: the compensation matrix is the 4-bit blob (its tiles run on the int8 units) instead of 16-bit fragments
-template <int ABITS, bool LRQ>
+// LRT: form of the compensation matrix -- SERQ_BF16 / SERQ_F16 fragments, or SERQ_I4: the 4-bit blob,
+// whose tiles run on the int8 units.  A compile-time choice: selected at run time inside the rank-r
+// loop, the f16 and bf16 MFMAs leave the compiler merging their results with register copies after
+// every MFMA.
+template <int ABITS, int LRT>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void serq_mfma_kernel(const MfmaParams p) {
   using T = Tile<ABITS>;
@@ -176,7 +175,7 @@ void serq_mfma_kernel(const MfmaParams p) {
   const int KT = KTF + (KTAIL ? 1 : 0);
   const int JB = (p.acc_out == nullptr) ? (p.r >> 4) : 0;
   const int LT = (JB + 3) >> 2;                      // low-rank tiles of 64 salient channels (16-bit R: up to 4 x 16)
-  constexpr bool lr_int = LRQ;                       // one weight-like fragment per tile and block
+  constexpr bool lr_int = LRT == SERQ_I4;            // one weight-like fragment per tile and block
   const int TT = KT + LT;
 
   // the tile's weight scales, times 2^-SH (exact), for the int -> float conversion
@@ -244,6 +243,10 @@ void serq_mfma_kernel(const MfmaParams p) {
   // low-rank tile lt (4 x 16 salient channels) into stage st
   auto issue_lr = [&](int lt, int st) {
     const uint32_t sb = lds0 + (uint32_t)st * STAGE + (uint32_t)wu * 1024;
+    // opaque copy of the thread index: the per-lane offsets below are recomputed here instead of
+    // being carried in registers through the main loop, where every register is taken
+    int tl = tid;
+    asm volatile("" : "+v"(tl));
     if constexpr (lr_int) {
       // wave w brings the fragment of block w to slot w; the other three loads of a wave repeat it
       // into unused slots so that every tile kind issues the same number of loads
@@ -267,16 +270,16 @@ void serq_mfma_kernel(const MfmaParams p) {
       const uint8_t* cbase = xbase + p.s_begin + 64 * lt;
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        int row = (tid + kThreads * i) >> 2;
-        int c = (tid & 3) ^ ((row >> 2) & 3);
+        int row = (tl + kThreads * i) >> 2;
+        int c = (tl & 3) ^ ((row >> 2) & 3);
         c = (64 * lt + 16 * c + 16 <= p.r) ? c : 0;  // a piece past the salient block is never read
         row = row < mrows ? row : mrows - 1;
         dma16(cbase, (uint32_t)row * rowbytes + 16u * c, sb + T::LR_R_BYTES + kWaves * 1024 * i);
       }
     } else {
       const uint8_t* cbase = xbase + ((p.s_begin + 64 * lt) >> 1);
-      int row = tid >> 1;
-      int c = (tid & 1) ^ ((row >> 3) & 1);
+      int row = tl >> 1;
+      int c = (tl & 1) ^ ((row >> 3) & 1);
       c = (64 * lt + 32 * c < p.r) ? c : 0;
       row = row < mrows ? row : mrows - 1;
       dma16(cbase, (uint32_t)row * rowbytes + 16u * c, sb + T::LR_R_BYTES);
@@ -321,16 +324,18 @@ void serq_mfma_kernel(const MfmaParams p) {
       }
     }
   };
-  auto load_lr_frags = [&](const uint8_t* st, int jb4, LrFrag& f) {
+  auto load_lr_r = [&](const uint8_t* st, int jb4, u4 (&r)[4]) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) f.r[i] = *(const u4*)(st + lr_r_off + (i * 4 + jb4) * 1024);
+    for (int i = 0; i < 4; ++i) r[i] = *(const u4*)(st + lr_r_off + (i * 4 + jb4) * 1024);
+  };
+  auto load_lr_x = [&](const uint8_t* st, int jb4, u2 (&x)[2]) {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       if constexpr (ABITS == 8) {
-        f.x[j] = *(const u2*)(st + lr_x_off[j] + 16 * (jb4 ^ lr_x_swz[j]) + 8 * g);
+        x[j] = *(const u2*)(st + lr_x_off[j] + 16 * (jb4 ^ lr_x_swz[j]) + 8 * g);
       } else {
-        f.x[j].x = *(const uint32_t*)(st + lr_x_off[j] + 16 * ((jb4 >> 1) ^ lr_x_swz[j]) + 8 * (jb4 & 1) + 4 * g);
-        f.x[j].y = 0;
+        x[j].x = *(const uint32_t*)(st + lr_x_off[j] + 16 * ((jb4 >> 1) ^ lr_x_swz[j]) + 8 * (jb4 & 1) + 4 * g);
+        x[j].y = 0;
       }
     }
   };
@@ -489,7 +494,7 @@ void serq_mfma_kernel(const MfmaParams p) {
 
     v16f accf[4][2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 4; ++i) {
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         const int cl = 32 * (blk0 + i) + 8 * q4 + 4 * g;          // channel within the tile
@@ -500,28 +505,32 @@ void serq_mfma_kernel(const MfmaParams p) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) accf[i][j][4 * q4 + e] = s4[e] * (float)acc[i][j][4 * q4 + e];
       }
+      fence();                                       // at most one block's scales in flight: the registers are full here
+    }
 
     // low-rank tiles: the last one may hold fewer than 4 blocks of 16 channels
-    const bool bf = p.r_dtype == SERQ_BF16;
-    auto mfma_lr = [&](const LrFrag& f) {
-      u4 xf[2];
+    using bf_t = std::integral_constant<bool, LRT != SERQ_F16>;
+    // 16-bit R: the 8 codes a lane holds for one block of 16 salient channels, as exact 16-bit floats
+    auto lr_codes = [&](auto bf_c, const u2 (&x)[2], u4 (&xf)[2]) {
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         int c[8];
-        if constexpr (ABITS == 8) codes_from_a8(f.x[j].x, f.x[j].y, c);
-        else codes_from_a4(f.x[j].x, c);
-        xf[j] = codes8_to_16bit(c, bf);
+        if constexpr (ABITS == 8) codes_from_a8(x[j].x, x[j].y, c);
+        else codes_from_a4(x[j].x, c);
+        xf[j] = codes8_to_16bit(c, decltype(bf_c)::value);
       }
+    };
+    auto mfma_lr = [&](auto bf_c, const u4 (&r)[4], const u4 (&xf)[2]) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         if (i < NBW) {
 #pragma unroll
           for (int j = 0; j < 2; ++j) {
-            if (bf)
-              accf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, f.r[i]),
+            if constexpr (decltype(bf_c)::value)
+              accf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, r[i]),
                                                                    __builtin_bit_cast(v8bf, xf[j]), accf[i][j], 0, 0, 0);
             else
-              accf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, f.r[i]),
+              accf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, r[i]),
                                                                   __builtin_bit_cast(v8h, xf[j]), accf[i][j], 0, 0, 0);
           }
         }
@@ -536,42 +545,63 @@ void serq_mfma_kernel(const MfmaParams p) {
       int rs_off = 0;
       asm volatile("" : "+v"(rs_off));
       const float* lrs_t = lrs + rs_off;
+      // the two MFMAs of (token block j, channel block i) into a scratch tile
+      auto product = [&](int i, const v4i& xb0, const v4i& xb1) {
+        const u4 rq = *(const u4*)(stp + (blk0 + i) * 1024 + l * 16);
+        v16i tq;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) tq[e] = 0;
+        tq = __builtin_amdgcn_mfma_i32_32x32x32_i8(widen(rq.x, rq.y), xb0, tq, 0, 0, 0);
+        tq = __builtin_amdgcn_mfma_i32_32x32x32_i8(widen(rq.z, rq.w), xb1, tq, 0, 0, 0);
+        return tq;
+      };
+      // accf[i][j] += rscale * 2^-SH * scratch tile
+      auto add_scaled = [&](auto i_c, auto j_c, const v16i& tq) {
+        constexpr int i = decltype(i_c)::value, j = decltype(j_c)::value;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int cl = 32 * (blk0 + i) + 8 * q4 + 4 * g;
+          const float4 rs = *(const float4*)(lrs_t + (cl < 256 ? cl : 0));
+          const float r4[4] = {rs.x, rs.y, rs.z, rs.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            accf[i][j][4 * q4 + e] = __builtin_fmaf(r4[e], (float)tq[4 * q4 + e], accf[i][j][4 * q4 + e]);
+        }
+        // pin the update here: left alone, the compiler sinks it below the hand-off and keeps
+        // every scratch tile and all the scales alive until then
+        asm volatile("" : "+v"(accf[i][j]));
+      };
+      v4i xb0[2], xb1[2];
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        v4i xb0, xb1;
         if constexpr (ABITS == 8) {
-          xb0 = *(const v4i*)(stp + lr_x_off[j] + 16 * ((2 * g) ^ lr_x_swz[j]));
-          xb1 = *(const v4i*)(stp + lr_x_off[j] + 16 * ((2 * g + 1) ^ lr_x_swz[j]));
+          xb0[j] = *(const v4i*)(stp + lr_x_off[j] + 16 * ((2 * g) ^ lr_x_swz[j]));
+          xb1[j] = *(const v4i*)(stp + lr_x_off[j] + 16 * ((2 * g + 1) ^ lr_x_swz[j]));
         } else {
           const u4 xp = *(const u4*)(stp + lr_x_off[j] + 16 * (g ^ lr_x_swz[j]));
-          xb0 = widen(xp.x, xp.y);
-          xb1 = widen(xp.z, xp.w);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          if (i < NBW) {
-            const u4 rq = *(const u4*)(stp + (blk0 + i) * 1024 + l * 16);
-            v16i tq;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) tq[e] = 0;
-            tq = __builtin_amdgcn_mfma_i32_32x32x32_i8(widen(rq.x, rq.y), xb0, tq, 0, 0, 0);
-            tq = __builtin_amdgcn_mfma_i32_32x32x32_i8(widen(rq.z, rq.w), xb1, tq, 0, 0, 0);
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-              const int cl = 32 * (blk0 + i) + 8 * q4 + 4 * g;
-              const float4 rs = *(const float4*)(lrs_t + (cl < 256 ? cl : 0));
-              const float r4[4] = {rs.x, rs.y, rs.z, rs.w};
-#pragma unroll
-              for (int e = 0; e < 4; ++e)
-                accf[i][j][4 * q4 + e] = __builtin_fmaf(r4[e], (float)tq[4 * q4 + e], accf[i][j][4 * q4 + e]);
-            }
-          }
-          // pin the update here: left alone, the compiler sinks it below the hand-off and keeps
-          // four scratch tiles and all their scales alive until then
-          if (i < NBW) asm volatile("" : "+v"(accf[i][j]));
-          fence();
+          xb0[j] = widen(xp.x, xp.y);
+          xb1[j] = widen(xp.z, xp.w);
         }
       }
+      // software pipeline over the 2*NBW products: the MFMAs of the next one are issued before the
+      // current scratch tile is converted, so the matrix unit works while the VALU scales
+      v16i cur = product(0, xb0[0], xb1[0]);
+      fence();
+      auto stage = [&](auto p_c) {
+        constexpr int pidx = decltype(p_c)::value;            // product pidx = (i = pidx / 2, j = pidx % 2)
+        if constexpr (pidx < 2 * NBW) {
+          v16i nxt = cur;
+          if constexpr (pidx + 1 < 2 * NBW) nxt = product((pidx + 1) / 2, xb0[(pidx + 1) % 2], xb1[(pidx + 1) % 2]);
+          fence();
+          add_scaled(std::integral_constant<int, pidx / 2>{}, std::integral_constant<int, pidx % 2>{}, cur);
+          fence();
+          cur = nxt;
+        }
+      };
+      stage(std::integral_constant<int, 0>{}); stage(std::integral_constant<int, 1>{});
+      stage(std::integral_constant<int, 2>{}); stage(std::integral_constant<int, 3>{});
+      stage(std::integral_constant<int, 4>{}); stage(std::integral_constant<int, 5>{});
+      stage(std::integral_constant<int, 6>{}); stage(std::integral_constant<int, 7>{});
     };
     // low-rank tiles; during them every refill is another low-rank tile
     fence();
@@ -580,12 +610,21 @@ void serq_mfma_kernel(const MfmaParams p) {
         lr_tile_int(stage_ptr(st));
         fence();
       } else {
+        // per block of 16 channels: R fragments from LDS, 8 MFMAs, and -- while those run -- the
+        // conversion of the next block's token codes
         const int njb = (JB - 4 * lt) < 4 ? (JB - 4 * lt) : 4;
+        u2 xr[2];
+        u4 xf[2];
+        load_lr_x(stage_ptr(st), 0, xr);
+        lr_codes(bf_t{}, xr, xf);
         for (int jb4 = 0; jb4 < njb; ++jb4) {
-          LrFrag G;
-          load_lr_frags(stage_ptr(st), jb4, G);
+          u4 rr[4];
+          load_lr_r(stage_ptr(st), jb4, rr);
+          const bool more = jb4 + 1 < njb;
+          if (more) load_lr_x(stage_ptr(st), jb4 + 1, xr);
           fence();
-          mfma_lr(G);
+          mfma_lr(bf_t{}, rr, xf);
+          if (more) lr_codes(bf_t{}, xr, xf);
           fence();
         }
       }
@@ -717,14 +756,19 @@ int launch_mfma(const LinearArgs& a, hipStream_t st) {
   const long long tiles = (long long)p.tiles_m * p.tiles_n;
   if (tiles > 0x7fffffffLL) return SERQ_ESHAPE;
   dim3 grid((unsigned)tiles), block(kThreads);
-  const bool lrq = p.r > 0 && p.r_dtype == SERQ_I4 && p.acc_out == nullptr;
+  const bool has_lr = p.r > 0 && p.acc_out == nullptr;
+  const int lrt = !has_lr ? SERQ_BF16 : p.r_dtype;     // without a compensation matrix any instantiation will do
+#define SERQ_MFMA_LAUNCH(AB, LRT) hipLaunchKernelGGL((serq_mfma_kernel<AB, LRT>), grid, block, 0, st, p)
   if (a.abits == 8) {
-    if (lrq) hipLaunchKernelGGL((serq_mfma_kernel<8, true>), grid, block, 0, st, p);
-    else hipLaunchKernelGGL((serq_mfma_kernel<8, false>), grid, block, 0, st, p);
+    if (lrt == SERQ_I4) SERQ_MFMA_LAUNCH(8, SERQ_I4);
+    else if (lrt == SERQ_F16) SERQ_MFMA_LAUNCH(8, SERQ_F16);
+    else SERQ_MFMA_LAUNCH(8, SERQ_BF16);
   } else {
-    if (lrq) hipLaunchKernelGGL((serq_mfma_kernel<4, true>), grid, block, 0, st, p);
-    else hipLaunchKernelGGL((serq_mfma_kernel<4, false>), grid, block, 0, st, p);
+    if (lrt == SERQ_I4) SERQ_MFMA_LAUNCH(4, SERQ_I4);
+    else if (lrt == SERQ_F16) SERQ_MFMA_LAUNCH(4, SERQ_F16);
+    else SERQ_MFMA_LAUNCH(4, SERQ_BF16);
   }
+#undef SERQ_MFMA_LAUNCH
   return hipGetLastError() == hipSuccess ? SERQ_OK : SERQ_EHIP;
 }
 
