@@ -166,7 +166,7 @@ int serq_quantize_act(const void* X, int x_dtype, const float* s_inv,
  * (s_begin + 64*ceil(r/64) <= K; the codes past r meet zero weights).
  *   Y [M,N] in y_dtype (fp32/fp16/bf16), row stride ldy elements (multiple of 8).
  *   workspace: serq_workspace_bytes(...) bytes prepared by serq_workspace_init
- *   (needed only when the skinny path splits K; pass NULL/0 to forbid that).
+ * (the decode path uses it when it cuts K into slices; pass NULL/0 to forbid that).
  *   flags: SERQ_PATH_* | SERQ_FLAG_*.
  */
 int serq_linear(const void* Xq, const float* scale, int abits,

@@ -68,13 +68,9 @@ size_t serq_packed_lowrank_q4_bytes(int64_t N, int r) {
 }
 
 size_t serq_workspace_bytes(int64_t M, int64_t N, int64_t K, int r, int abits) {
-  (void)r; (void)abits;
+  (void)M; (void)r; (void)abits;
   if (check_nk(N, K) != SERQ_OK || M < 0) return 0;
-  // the skinny path's split-K partial sums and arrival counters; sized for the
-  // largest factor the flags can request
-  int s = skinny_splitk_auto((int)(M > 32 ? 32 : M), (int)N, (int)K);
-  if (s < 8) s = 8;
-  return skinny_workspace_bytes((int)N, s);
+  return skinny_workspace_bytes((int)N);             // where the slices of a channel block meet (decode path)
 }
 
 int serq_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {

@@ -162,8 +162,7 @@ struct LinearArgs {
   int splitk; int groupm; int coltiles; int skinny_waves;
 };
 
-int skinny_splitk_auto(int M, int N, int K);
-size_t skinny_workspace_bytes(int N, int splitk);
+size_t skinny_workspace_bytes(int N);
 int launch_skinny(const LinearArgs& a, hipStream_t st);
 int launch_mfma(const LinearArgs& a, hipStream_t st);
 int launch_quantize_act(const void* X, int x_dtype, const float* s_inv, int64_t M, int K, int64_t ldx,

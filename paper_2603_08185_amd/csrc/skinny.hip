@@ -5,8 +5,11 @@
 //   Y[m,n] = scale[m] * ( wscale[n] * sum_k Xq[m,k] Wq[n,k] + sum_j Xq[m,S_j] R[j,n] )
 //
 // Work decomposition: a workgroup of 4 or 8 waves owns one block of 32 output
-// channels and one slice of K (the host splits K only when N alone gives too
-// few workgroups).  The 1-KiB weight fragments of the block are contiguous in
+// channels and all of K, or one slice of it when N alone gives fewer workgroups
+// than there are CUs.  (Cutting only the blocks that do not deal out evenly --
+// 344 blocks on 256 CUs: 256 whole blocks and 88 in slices -- was tried and
+// measured no faster than leaving 88 CUs with two blocks.)  The 1-KiB weight
+// fragments of a block are contiguous in
 // memory; wave w of W takes the groups w, w+W, ... of four or eight consecutive
 // fragments: one coalesced 16-byte load per lane and fragment, the whole group
 // in flight before its first fragment is used.
@@ -31,13 +34,22 @@
 // accumulator.
 //
 // The waves are combined through LDS in a fixed order (each wave parks its
-// partial sums in its own region: one barrier in the whole kernel).  With a
-// split K the workgroup stores its partial sums (INT32 for the main term, fp32
-// for the low-rank term, which only slice 0 computes) to the workspace and a
-// second, small kernel adds the slices in a fixed order and applies the
-// epilogue -- the kernel boundary is the only synchronisation, so no
-// device-wide fences or atomics are needed and results are run-to-run
-// identical.
+// partial sums in its own region: one barrier per workgroup).  The workgroups
+// of a sliced block meet in the workspace, one 64-bit word per output: a thread
+// adds 2^40 + (its INT32 partial sum) with one returning agent-scope atomic; the
+// old value tells it how many slices had arrived (bits 40 and up; the signed sum
+// below stays within +-2^39) and what they summed to.  The thread that finds all
+// the others there has the total in hand, applies the epilogue and stores zero
+// back (the workspace is clean again for the next launch).  One round trip, no
+// barrier, no counter -- three dependent round trips (add, ticket, fetch)
+// measured slower than the imbalance they were meant to cure, because under a
+// saturated memory system each costs microseconds -- and only read-modify-write
+// atomics touch that memory, so no cache write-back or invalidate is needed
+// (device-wide fences cost an L2 write-back each on this part and made an earlier
+// version 10-30x slower).  Every slice computes the rank-r term itself (8 KiB of
+// R per slice, a few per cent more traffic) so that whichever slice arrives last
+// can finish alone.  Integer addition is associative and every slice computes
+// the same rank-r sums, so results are run-to-run identical.
 #include "serq_device.h"
 
 namespace serq {
@@ -50,11 +62,10 @@ struct SkinnyParams {
   int M, N, K;
   void* Y; int y_dtype; int64_t ldy;
   int32_t* acc_out; int64_t ldacc;
-  int splitk;
   int region;                           // bytes of LDS per wave
   int lrx_off;                          // where in its region a wave keeps the token codes of a 4-bit R fragment
   const float* rscale;                  // scales of a 4-bit compensation matrix (r_dtype == SERQ_I4)
-  int32_t* part_i; int32_t* part_l;     // [N/32][splitk][1024] INT32 sums; [N/32][1024] rank-r sums (fp32 bits or INT32)
+  unsigned long long* ws;               // [N/32][1024]: where the slices of a block meet, all zero between launches
 };
 
 // y for (token m, channel n) from the two sums; one store
@@ -109,9 +120,10 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu((kG
   const int tid = threadIdx.x;
   const int w = tid >> 6, l = tid & 63;
   const int m = l & 31, g = l >> 5;
-  const int nb = blockIdx.x, ks = blockIdx.y;          // grid: (channel blocks, K slices)
+  // grid: (channel blocks, K slices); slices of kb_per fragments, the first kb_rem of them one longer
+  const int nb = blockIdx.x, ks = blockIdx.y, ns = gridDim.y;
   const int KB = hK >> 6;
-  const int kb0 = ks * kb_per + (ks < kb_rem ? ks : kb_rem);   // the first kb_rem slices are one fragment longer
+  const int kb0 = ks * kb_per + (ks < kb_rem ? ks : kb_rem);
   const int kb1 = kb0 + kb_per + (ks < kb_rem ? 1 : 0);
   const size_t rowbytes = (size_t)hK * ABITS / 8;
 
@@ -129,7 +141,7 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu((kG
   // the token codes of the rank-r term (slice 0 only; one fragment of R per wave is requested up front):
   // blocks of 16 salient channels for a 16-bit R, of 64 for a 4-bit one ...
   const bool has_lr = p.r > 0 && p.acc_out == nullptr;
-  const bool lr_here = has_lr && ks == 0;
+  const bool lr_here = has_lr;                          // every slice computes it: whichever finishes the block needs it
   const bool lr_int = p.r_dtype == SERQ_I4;
   const int JB = lr_int ? (p.r + 63) >> 6 : p.r >> 4;  // fragments of R per channel block
   const bool bf = p.r_dtype == SERQ_BF16;
@@ -163,7 +175,7 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu((kG
   for (int q = 0; q < NQ; ++q) {
     const int id = tid + q * kThreads;
     sc_m[q] = sc_n[q] = sc_r[q] = 0.0f;
-    if (p.acc_out == nullptr && gridDim.y == 1 && (id >> 5) < hM) {
+    if (p.acc_out == nullptr && (id >> 5) < hM) {       // any workgroup may be the one that finishes its block
       sc_m[q] = p.scale[id >> 5];
       sc_n[q] = p.wscale[nb * 32 + (id & 31)];
       if (has_lr && lr_int) sc_r[q] = p.rscale[nb * 32 + (id & 31)];
@@ -296,100 +308,95 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu((kG
     }
   }
   __syncthreads();
+  int tot_i[NQ], tot_l[NQ];                               // rank-r sums as words: fp32 bits or INT32
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) {
+    const int id = tid + q * kThreads;
+    const int nl = id & 31, mt = id >> 5;
+    tot_i[q] = tot_l[q] = 0;
+    if (mt >= hM) continue;
+    const int src = mt * kRedPitch + nl;
+#pragma unroll
+    for (int ww = 0; ww < kWaves; ++ww) tot_i[q] += *reinterpret_cast<const int*>(lds + (size_t)ww * hregion + 4 * src);
+    if (lr_here) {
+      int li = 0;
+      float lf = 0.0f;
+      for (int ww = 0; ww < nwl; ++ww) {
+        const int word = *reinterpret_cast<const int*>(lds + (size_t)ww * hregion + 4 * (hM * kRedPitch + src));
+        if (lr_int) li += word;
+        else lf += __int_as_float(word);
+      }
+      tot_l[q] = lr_int ? li : __float_as_int(lf);
+    }
+  }
+
+  unsigned long long* wsb = p.ws + (size_t)nb * 1024;
 #pragma unroll
   for (int q = 0; q < NQ; ++q) {
     const int id = tid + q * kThreads;
     const int nl = id & 31, mt = id >> 5;
     if (mt >= hM) continue;
-    const int src = mt * kRedPitch + nl;
-    int tot_i = 0, tot_li = 0;
-    float tot_f = 0.0f;
-#pragma unroll
-    for (int ww = 0; ww < kWaves; ++ww) tot_i += *reinterpret_cast<const int*>(lds + (size_t)ww * hregion + 4 * src);
-    if (lr_here)
-      for (int ww = 0; ww < nwl; ++ww) {
-        const int word = *reinterpret_cast<const int*>(lds + (size_t)ww * hregion + 4 * (hM * kRedPitch + src));
-        if (lr_int) tot_li += word;
-        else tot_f += __int_as_float(word);
-      }
-    if (p.splitk > 1) {
-      // partial sums of this slice; the reduce kernel finishes the job
-      p.part_i[((size_t)nb * p.splitk + ks) * 1024 + id] = tot_i;
-      if (lr_here) p.part_l[(size_t)nb * 1024 + id] = lr_int ? tot_li : __float_as_int(tot_f);
-    } else {
-      const float lr = lr_int ? sc_r[q] * (float)(tot_li >> SH) : tot_f;
-      finish(p, mt, nb * 32 + nl, tot_i >> SH, lr, sc_m[q], sc_n[q]);   // exact shifts: the sums are multiples of 2^SH
+    int total = tot_i[q];
+    if (ns > 1) {                                         // uniform over the workgroup
+      const long long mine = (1ll << 40) + (long long)tot_i[q];
+      const long long old = (long long)__hip_atomic_fetch_add(wsb + id, (unsigned long long)mine, __ATOMIC_RELAXED,
+                                                              __HIP_MEMORY_SCOPE_AGENT);
+      const long long arrived = (old + (1ll << 39)) >> 40;
+      if (arrived != ns - 1) continue;                    // someone after us finishes this output
+      total += (int)(old - (arrived << 40));
+      __hip_atomic_store(wsb + id, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    const float lr = !has_lr ? 0.0f : (lr_int ? sc_r[q] * (float)(tot_l[q] >> SH) : __int_as_float(tot_l[q]));
+    finish(p, mt, nb * 32 + nl, total >> SH, lr, sc_m[q], sc_n[q]);   // exact shifts: the sums are multiples of 2^SH
   }
-}
-
-// second kernel of a split-K launch: one workgroup per block of 32 channels
-template <int ABITS>
-__global__ __launch_bounds__(1024) void serq_skinny_reduce_kernel(const SkinnyParams p) {
-  constexpr int SH = (ABITS == 8) ? 4 : 8;
-  const int tid = threadIdx.x;
-  const int nb = blockIdx.x;
-  const int mt = tid >> 5;
-  if (mt >= p.M) return;
-  int tot_i = 0;
-  for (int s = 0; s < p.splitk; ++s) tot_i += p.part_i[((size_t)nb * p.splitk + s) * 1024 + tid];
-  const bool has_lr = p.r > 0 && p.acc_out == nullptr;
-  const int n = nb * 32 + (tid & 31);
-  float tot_f = 0.0f;
-  if (has_lr) {
-    const int word = p.part_l[(size_t)nb * 1024 + tid];
-    tot_f = p.r_dtype == SERQ_I4 ? p.rscale[n] * (float)(word >> SH) : __int_as_float(word);
-  }
-  const bool scaled = p.acc_out == nullptr;
-  finish(p, mt, n, tot_i >> SH, tot_f, scaled ? p.scale[mt] : 0.0f, scaled ? p.wscale[n] : 0.0f);
 }
 
 }  // namespace
 
-int skinny_splitk_auto(int M, int N, int K) {
-  (void)M;
-  const int nblk = N / 32;
-  const int KB = K / 64;
-  int s = (128 + nblk - 1) / nblk;           // 128 workgroups already keep half the CUs streaming; a split costs a second launch
-  const int smax = KB / 16 > 0 ? KB / 16 : 1;          // keep >= 16 fragments per slice
-  if (s > smax) s = smax;
-  if (s > 16) s = 16;
-  if (s < 1) s = 1;
-  return s;
-}
-
-size_t skinny_workspace_bytes(int N, int splitk) {
-  const size_t nblk = (size_t)N / 32;
-  if (splitk <= 1) return 256;
-  return nblk * (size_t)splitk * 1024 * 4 + nblk * 1024 * 4;
+size_t skinny_workspace_bytes(int N) {
+  return (size_t)N / 32 * 1024 * 8;                      // one 64-bit word per output of a 32-token block
 }
 
 int launch_skinny(const LinearArgs& a, hipStream_t st) {
+  static int ncu = 0;
+  if (ncu == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    ncu = n;
+  }
   SkinnyParams p;
   p.Xq = a.Xq; p.scale = a.scale; p.Wq = a.Wq; p.wscale = a.wscale;
   p.Rp = a.Rp; p.r_dtype = a.r_dtype; p.s_begin = a.s_begin; p.r = a.Rp ? a.r : 0;
   p.M = a.M; p.N = a.N; p.K = a.K;
   p.Y = a.Y; p.y_dtype = a.y_dtype; p.ldy = a.ldy;
   p.acc_out = a.acc_out; p.ldacc = a.ldacc;
-  int splitk = a.splitk > 0 ? a.splitk : skinny_splitk_auto(a.M, a.N, a.K);
-  const int KB = a.K / 64;
-  if (splitk > KB) splitk = KB;
-  const size_t nblk = (size_t)a.N / 32;
-  if (splitk > 1) {
-    if (a.workspace == nullptr || a.workspace_bytes < skinny_workspace_bytes(a.N, splitk)) {
-      if (a.splitk > 0) return SERQ_EWORKSPACE;      // an explicit request cannot be honoured
-      splitk = 1;                                     // auto: fall back to no split
-    }
-  }
-  p.splitk = splitk;
-  p.part_i = splitk > 1 ? (int32_t*)a.workspace : nullptr;
-  p.part_l = splitk > 1 ? (int32_t*)((char*)a.workspace + nblk * (size_t)splitk * 1024 * 4) : nullptr;
   p.rscale = a.rscale;
+  const int KB = a.K / 64;
+  const int nblk = a.N / 32;
+  const bool have_ws = a.workspace != nullptr && a.workspace_bytes >= skinny_workspace_bytes(a.N);
 
-  // Waves per workgroup: 8 once the slice gives each of them a group of fragments, else 4.  (16-wave
-  // workgroups measured slower: their registers and LDS allow one workgroup per CU where two or three
-  // smaller ones overlap each other's start-up and epilogue.)
-  const int KBs = (KB + splitk - 1) / splitk;           // longest slice, in fragments
+  // K slices per block: as requested by the flags, else as many as it takes to have about one
+  // workgroup per CU when there are fewer blocks than CUs (needs the workspace; without it, none).
+  int nsplit = 1;
+  if (a.splitk > 1) {
+    if (!have_ws) return SERQ_EWORKSPACE;               // an explicit request cannot be honoured
+    nsplit = a.splitk;
+  } else if (a.splitk == 0 && have_ws && nblk < ncu) {
+    nsplit = ncu / nblk;
+    const int smax = KB / 8;                            // a slice keeps at least 8 fragments
+    if (nsplit > smax) nsplit = smax;
+    if (nsplit > 16) nsplit = 16;
+  }
+  if (nsplit > KB) nsplit = KB;
+  if (nsplit < 1) nsplit = 1;
+  p.ws = have_ws ? (unsigned long long*)a.workspace : nullptr;
+
+  // Waves per workgroup: 8 once the longest piece gives each of them a group of fragments, else 4.
+  // (16-wave workgroups measured slower: their registers and LDS allow one workgroup per CU where two
+  // or three smaller ones overlap each other's start-up and epilogue.)
+  const int KBs = (KB + nsplit - 1) / nsplit;           // longest slice, in fragments
   int nw = a.skinny_waves;
   if (nw != 4 && nw != 8) nw = KBs >= 32 ? 8 : 4;
   // Fragments per group: 8 when every wave gets a full group of 8 and the token rows of such a group
@@ -412,8 +419,8 @@ int launch_skinny(const LinearArgs& a, hipStream_t st) {
   p.region = region;
   const size_t lds_bytes = (size_t)region * nw;
 
-  dim3 grid((unsigned)nblk, (unsigned)splitk), block((unsigned)nw * 64);
-#define SERQ_SKINNY_LAUNCH(AB, NW, G) hipLaunchKernelGGL((serq_skinny_kernel<AB, NW, G>), grid, block, lds_bytes, st, p.Xq, p.Wq, p.K, p.M, KB / splitk, KB % splitk, p.region, p)
+  dim3 grid((unsigned)nblk, (unsigned)nsplit), block((unsigned)nw * 64);
+#define SERQ_SKINNY_LAUNCH(AB, NW, G) hipLaunchKernelGGL((serq_skinny_kernel<AB, NW, G>), grid, block, lds_bytes, st, p.Xq, p.Wq, p.K, p.M, KB / nsplit, KB % nsplit, p.region, p)
   if (a.abits == 8) {
     if (nw == 4) { if (grp == 4) SERQ_SKINNY_LAUNCH(8, 4, 4); else SERQ_SKINNY_LAUNCH(8, 4, 8); }
     else { if (grp == 4) SERQ_SKINNY_LAUNCH(8, 8, 4); else SERQ_SKINNY_LAUNCH(8, 8, 8); }
@@ -423,12 +430,6 @@ int launch_skinny(const LinearArgs& a, hipStream_t st) {
   }
 #undef SERQ_SKINNY_LAUNCH
   if (hipGetLastError() != hipSuccess) return SERQ_EHIP;
-  if (splitk > 1) {
-    dim3 grid2((unsigned)nblk), block2(1024);
-    if (a.abits == 8) hipLaunchKernelGGL(serq_skinny_reduce_kernel<8>, grid2, block2, 0, st, p);
-    else hipLaunchKernelGGL(serq_skinny_reduce_kernel<4>, grid2, block2, 0, st, p);
-    if (hipGetLastError() != hipSuccess) return SERQ_EHIP;
-  }
   return SERQ_OK;
 }
 
