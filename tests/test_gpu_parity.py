@@ -378,6 +378,15 @@ def test_layer_q4r_small_shapes(abits, out_dtype, M, K, N, r, path):
         _run_layer_q4r(spec, path=path, groupm=1)
 
 
+@pytest.mark.parametrize("abits", [4, 8])
+@pytest.mark.parametrize("M,path,groupm", [(2, serq.PATH_SKINNY, 1), (32, serq.PATH_SKINNY, 2), (70, serq.PATH_MFMA, 0)])
+def test_layer_large_rank(abits, M, path, groupm):
+    # more rank fragments than a workgroup has waves (decode kernel) / ten rank-r tiles (GEMM kernel)
+    spec = _small_spec(abits, M, 1024, 96, 640)
+    _run_layer(spec, R_mode="random", path=path, groupm=groupm, check_pack=False)
+    _run_layer_q4r(spec, path=path, groupm=groupm)
+
+
 @pytest.mark.parametrize("path", [serq.PATH_SKINNY, serq.PATH_MFMA])
 def test_layer_q4r_salient_block_offset(path):
     spec = _small_spec(8, 9, 512, 64, 80)
