@@ -49,8 +49,8 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, 8 TB/s
 # HBM traffic of one serq_linear launch of the benchmark workload, from two counter runs
 # (FETCH_SIZE, then WRITE_SIZE) of this script scaled by the same counters of --calibrate-copy;
 # the runs and the arithmetic are in profiles/serq_mfma_kernel_cfg3_up_M4096_hbm_traffic.md.
-# 103 310 FETCH_SIZE counts x 2048 B + 88 082 WRITE_SIZE counts x 1024 B.
-LINEAR_TRAFFIC_BYTES = 103310 * 2048 + 88082 * 1024
+# 103 150 FETCH_SIZE counts x 2048 B + 88 088 WRITE_SIZE counts x 1024 B.
+LINEAR_TRAFFIC_BYTES = 103150 * 2048 + 88088 * 1024
 
 
 def _events(n):
