@@ -15,7 +15,10 @@ would otherwise sit entirely inside that ramp.
 Prints ONE JSON line.  `value` is 2*M*N*K / step time in TOPS.  `roofline`
 prices the dominant kernel (serq_linear) against the int8 MFMA peak using its
 own launch durations, measured with HIP events on the launch stream inside the
-timed region.  `decode` reports the M = 1 weight-streaming kernel in GB/s with
+timed region.  `measured_peaks` says what the part sustains with nothing in the way (an MFMA-only
+loop on this layer's operand bytes; read-only kernels), and the fractions of those
+are reported next to the fractions of the datasheet peaks.
+`decode` reports the M = 1 weight-streaming kernel in GB/s with
 the weight copies rotated so that the working set exceeds the Infinity Cache;
 the launches are replayed from a HIP graph, as a serving loop would issue them.
 `cpu_baseline` is the NumPy oracle timed on whole passes (about 10 s) over the same
@@ -109,7 +112,7 @@ def bench_prefill(steps: int, warmup: int):
         "tops_step": ops / (total_ms / steps * 1e-3) / 1e12,
         "tops_linear": ops / (l_ms * 1e-3) / 1e12,
         "quant_gbs": qbytes / (q_ms * 1e-3) / 1e9,
-        "layer": (L, pk),
+        "layer": (L, pk), "Xq": Xq,
     }
 
 
@@ -173,6 +176,33 @@ def bench_decode(L, pk, reps: int = 5):
             "us_cache_warm": warm * 1e3, "gbs_cache_warm": b / (warm * 1e-3) / 1e9,
             "us_hbm_stream_launch": cold_stream * 1e3,
             "frac_hbm_peak": b / (cold * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+
+def measured_peaks(pk, Xq, spec):
+    """What this part sustains with nothing in the way: an MFMA-only loop fed with this layer's own operand
+    bytes (weight codes widened to 16q as the kernel feeds them, token codes as they are), and read-only kernels
+    of the decode call's size (rotating over > 640 MB, replayed from a graph) and of 1 GiB."""
+    dev = "cuda:0"
+    w = serq.unpack_weights(pk.Wq, spec.N, spec.K)[:256, :64].to(torch.int16) * 16
+    x = serq.unpack_act(Xq, spec.abits, spec.M, spec.K)[:256, :64]
+    ops_buf = torch.cat([w.to(torch.int8).reshape(256, 4, 16), x.reshape(256, 4, 16)], dim=1).contiguous()
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    iters, wgs = 2000, 1024
+    run = lambda: serq.bench_mfma_peak(ops_buf, iters, wgs, sink)
+    spin_up(run, 0.1)
+    t_us = _time_launches(lambda i: run(), 5)
+    mfma_tops = 2.0 * 32 ** 3 * 16 * iters * 4 * wgs / t_us / 1e6
+    nbytes = int(decode_bytes(workloads.config3("up", 1))) // 16 * 16
+    ncopy = int(np.ceil(640e6 / nbytes))
+    big = torch.empty(max(ncopy * nbytes, 1 << 30), dtype=torch.uint8, device=dev).fill_(1)
+    views = [big[i * nbytes:(i + 1) * nbytes] for i in range(ncopy)]
+    rd = lambda i: serq.bench_read(views[i % ncopy], nbytes, 2048, sink)
+    spin_up(lambda: rd(0), 0.05)
+    small_us = _time_launches(rd, 4 * ncopy, graph=True)
+    large_us = _time_launches(lambda i: serq.bench_read(big, 1 << 30, 16384, sink), 3)
+    return {"mfma_int8_tops": round(mfma_tops, 1), "mfma_operands": "this layer's codes (weights x16, tokens)",
+            "read_gbs_decode_size": round(nbytes / small_us / 1e3, 1), "read_bytes_decode_size": nbytes,
+            "read_gbs_1GiB": round((1 << 30) / large_us / 1e3, 1)}
 
 
 def cpu_baseline(L, n_tokens: int = 4096, min_seconds: float = 10.0):
@@ -350,9 +380,13 @@ def main():
         "quantize_act": {"ms": round(pre["quant_ms"], 5), "gbs": round(pre["quant_gbs"], 1),
                          "frac_hbm_peak": round(pre["quant_gbs"] / HBM_PEAK_GBS, 4)},
     }
+    mp = measured_peaks(pk, pre["Xq"], spec)
+    out["measured_peaks"] = mp
+    out["roofline"]["frac_of_measured_mfma_peak"] = round(pre["tops_linear"] / mp["mfma_int8_tops"], 4)
     if not a.no_decode:
         d = bench_decode(L, pk)
-        out["decode"] = {k: (round(v, 3) if isinstance(v, float) else v) for k, v in d.items()}
+        d["frac_of_measured_read_peak"] = d["gbs_hbm"] / mp["read_gbs_decode_size"]
+        out["decode"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in d.items()}
     if not a.no_cpu:
         cb, _ = cpu_baseline(L)
         cb["value"] = round(cb["value"], 5)

@@ -184,6 +184,21 @@ int serq_gemm_i32(const void* Xq, int abits, const void* Wq,
                   int32_t* acc_out, int64_t ldacc,
                   void* workspace, size_t workspace_bytes, int flags, void* stream);
 
+/*
+ * Measuring sticks for benchmarks (no part of the layer; see the roofline discussion of Sec. 4.3's
+ * latency tables only in so far as they say what "peak" means on this part).
+ *
+ * serq_bench_mfma_peak: `workgroups` x 4 waves each run `iters` x 16 int8 MFMAs (32x32x32) on operands
+ *   held in registers: 2 * 32*32*32 * 16 * iters * 4 * workgroups integer operations and nothing else.
+ *   operands: 32 KiB (256 threads x 8 x 16 bytes: 4 A and 4 B operand registers per thread), device memory;
+ *   the achieved rate depends on these bytes.  sink: 4 bytes of device memory (never written in practice).
+ * serq_bench_read: reads [src, src + bytes) once with 16-byte loads from `workgroups` workgroups and
+ *   does nothing else.  bytes a multiple of 16.
+ * Both return SERQ_OK or a negative code; both only launch (asynchronous on `stream`).
+ */
+int serq_bench_mfma_peak(const void* operands, int iters, int workgroups, void* sink, void* stream);
+int serq_bench_read(const void* src, size_t bytes, int workgroups, void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

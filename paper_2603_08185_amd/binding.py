@@ -44,6 +44,8 @@ SIGNATURES = {
     "serq_linear": (_i, [_vp, _vp, _i, _vp, _vp, _i, _i, _vp, _i, _i64, _i64, _i64, _vp, _i, _i64,
                          _vp, _sz, _i, _vp]),
     "serq_gemm_i32": (_i, [_vp, _i, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _sz, _i, _vp]),
+    "serq_bench_mfma_peak": (_i, [_vp, _i, _i, _vp, _vp]),
+    "serq_bench_read": (_i, [_vp, _sz, _i, _vp, _vp]),
 }
 
 _lib = None
@@ -234,3 +236,14 @@ def gemm_i32(Xq: torch.Tensor, abits: int, Wq: torch.Tensor, M: int, N: int, K: 
                              _ptr(ws), 0 if ws is None else ws.numel(), flags_, _stream())
     _check("serq_gemm_i32", rc)
     return acc
+
+
+def bench_mfma_peak(operands: torch.Tensor, iters: int, workgroups: int, sink: torch.Tensor) -> None:
+    """serq_bench_mfma_peak: nothing but int8 MFMAs on the given 32 KiB of operand bytes."""
+    assert operands.numel() * operands.element_size() >= 32768
+    _check("serq_bench_mfma_peak", lib().serq_bench_mfma_peak(_ptr(operands), iters, workgroups, _ptr(sink), _stream()))
+
+
+def bench_read(src: torch.Tensor, nbytes: int, workgroups: int, sink: torch.Tensor) -> None:
+    """serq_bench_read: nothing but one read of the first nbytes of src."""
+    _check("serq_bench_read", lib().serq_bench_read(_ptr(src), nbytes, workgroups, _ptr(sink), _stream()))

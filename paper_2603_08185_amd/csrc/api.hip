@@ -231,4 +231,19 @@ int serq_gemm_i32(const void* Xq, int abits, const void* Wq,
   return linear_common(a, M, N, K, flags, stream);
 }
 
+int serq_bench_mfma_peak(const void* operands, int iters, int workgroups, void* sink, void* stream) {
+  if (!operands || !sink) return SERQ_ENULL;
+  if (iters < 0 || workgroups <= 0 || workgroups > (1 << 20)) return SERQ_ESHAPE;
+  if (!aligned16(operands) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return SERQ_EALIGN;
+  return launch_mfma_peak(operands, iters, workgroups, sink, (hipStream_t)stream);
+}
+
+int serq_bench_read(const void* src, size_t bytes, int workgroups, void* sink, void* stream) {
+  if (!src || !sink) return SERQ_ENULL;
+  if ((bytes % 16) != 0 || workgroups <= 0 || workgroups > (1 << 20)) return SERQ_ESHAPE;
+  if (!aligned16(src) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return SERQ_EALIGN;
+  if (bytes == 0) return SERQ_OK;
+  return launch_read_peak(src, bytes, workgroups, sink, (hipStream_t)stream);
+}
+
 }  // extern "C"

@@ -1,0 +1,78 @@
+// Two measuring sticks for the benchmark (not part of the layer): what this part sustains when it
+// does nothing but int8 MFMAs on operand bytes of the kind the layer feeds it, and what it sustains
+// when it does nothing but read.  The datasheet peaks (5.0 POP/s, 8 TB/s) are never reached by any
+// kernel here -- the part is power-limited under MFMA load and a read of tens of megabytes is over
+// before the memory system is in full swing -- so the benchmark reports fractions of both.
+#include "serq_device.h"
+
+namespace serq {
+namespace {
+
+// 16 independent 32x32x32 int8 MFMA accumulators per wave, operands from registers only.
+// `operands`: 8 x 16 bytes per thread of one 256-thread workgroup (4 A and 4 B operands), the same
+// for every workgroup.
+__global__ __launch_bounds__(256) void mfma_peak_kernel(const v4i* __restrict__ operands, int iters,
+                                                        int* __restrict__ sink) {
+  v16i acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0;
+  v4i a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    a[i] = operands[threadIdx.x * 8 + i];
+    b[i] = operands[threadIdx.x * 8 + 4 + i];
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i * 4 + j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i * 4 + j], 0, 0, 0);
+  }
+  int s = 0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s += acc[i][e];
+  if (s == 0x7fffffff) sink[0] = s;                     // keeps the loop alive; practically never taken
+}
+
+// Every 16-byte piece of [src, src + bytes) is read once; nothing else happens.
+__global__ __launch_bounds__(256) void read_peak_kernel(const u4* __restrict__ src, size_t n16, size_t per_wg,
+                                                        int* __restrict__ sink) {
+  const size_t base = (size_t)blockIdx.x * per_wg;
+  size_t end = base + per_wg;
+  if (end > n16) end = n16;
+  u4 acc = {0u, 0u, 0u, 0u};
+  for (size_t i = base + threadIdx.x; i < end; i += 256 * 4) {
+    u4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t j = i + 256 * u;
+      v[u] = j < end ? __builtin_nontemporal_load(src + j) : acc;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) acc ^= v[u];
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x12345678u) sink[0] = 1;   // keeps the loads alive
+}
+
+}  // namespace
+
+int launch_mfma_peak(const void* operands, int iters, int workgroups, void* sink, hipStream_t st) {
+  hipLaunchKernelGGL(mfma_peak_kernel, dim3((unsigned)workgroups), dim3(256), 0, st, (const v4i*)operands, iters,
+                     (int*)sink);
+  return hipGetLastError() == hipSuccess ? SERQ_OK : SERQ_EHIP;
+}
+
+int launch_read_peak(const void* src, size_t bytes, int workgroups, void* sink, hipStream_t st) {
+  const size_t n16 = bytes / 16;
+  const size_t per = (n16 + workgroups - 1) / workgroups;
+  hipLaunchKernelGGL(read_peak_kernel, dim3((unsigned)workgroups), dim3(256), 0, st, (const u4*)src, n16, per,
+                     (int*)sink);
+  return hipGetLastError() == hipSuccess ? SERQ_OK : SERQ_EHIP;
+}
+
+}  // namespace serq

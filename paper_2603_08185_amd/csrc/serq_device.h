@@ -168,6 +168,9 @@ int launch_mfma(const LinearArgs& a, hipStream_t st);
 int launch_quantize_act(const void* X, int x_dtype, const float* s_inv, int64_t M, int K, int64_t ldx,
                         int abits, void* Xq, float* scale, hipStream_t st);
 
+int launch_mfma_peak(const void* operands, int iters, int workgroups, void* sink, hipStream_t st);
+int launch_read_peak(const void* src, size_t bytes, int workgroups, void* sink, hipStream_t st);
+
 int pack_weights_impl(const void* W, int w_dtype, const float* s, const int32_t* perm_in, int N, int K, int r,
                       void* Wq_out, float* wscale_out, int32_t* perm_out, float* s_inv_out, void* R_out,
                       int r_dtype, void* Rp_out, hipStream_t st);
