@@ -22,7 +22,9 @@ reduction to a textbook matmul, the scale/2 rounding bound, permutation and
 flattening invariances, the r = 0 reduction, and the exact-residual identity
 main + compensation == Q(X) . [W_s ; deq(Q(W_r))]; for the 4-bit compensation
 matrix a hand-worked example, the integer-matrix reduction, the scale/2 bound
-and the reduction to `linear` with the dequantised matrix.  No function is unpinned.
+and the reduction to `linear` with the dequantised matrix; for MXFP4 the value
+table and tie cases of the format, hand-worked blocks, the power-of-two
+invariance, the error bound of the grid and brute force.  No function is unpinned.
 """
 from __future__ import annotations
 
@@ -200,6 +202,102 @@ def linear_q4r(Xq, scale, Wq, wscale, Rq, rscale, s_begin: int = 0, acc=None) ->
     y = (np.asarray(wscale, np.float64)[None, :] * acc.astype(np.float64)
          + np.asarray(rscale, np.float64)[None, :] * acc_r.astype(np.float64))
     return np.asarray(scale, np.float64)[:, None] * y
+
+
+# ---------------------------------------------------------------------------
+# MXFP4: the 4-bit Microscaling format the paper's W4A4 latency runs use
+# (Sec. 4.1; appendix on the MX format: blocks of 32 elements sharing one
+# 8-bit power-of-two scale taken from the block's maximum, elements in a 4-bit
+# floating-point format).  The arithmetic below follows the published OCP
+# Microscaling specification for MXFP4: element format E2M1 (values
+# +-{0, 0.5, 1, 1.5, 2, 3, 4, 6}), scale format E8M0.
+# ---------------------------------------------------------------------------
+MX_BLOCK = 32
+E2M1_VALUES = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], dtype=F32)
+_E2M1_MID = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0], dtype=F32)   # midpoints of neighbouring values
+
+
+def e2m1_round(t: np.ndarray) -> np.ndarray:
+    """Nearest E2M1 code (0..15: sign bit 8, magnitude index 0..7) of each element of t.
+
+    Round to nearest, ties to the code with an even mantissa bit (index 0, 2, 4, 6:
+    values 0, 1, 2, 4), magnitudes above 6 saturate to 6; zero keeps sign 0.
+    """
+    t = np.asarray(t, dtype=F32)
+    a = np.abs(t)
+    idx = np.searchsorted(_E2M1_MID, a, side="left")               # midpoints strictly below |t|
+    tie = (idx < 7) & (a == _E2M1_MID[np.minimum(idx, 6)])
+    idx = np.where(tie & (idx % 2 == 1), idx + 1, idx)             # at a tie idx is the lower neighbour
+    idx = np.minimum(idx, 7)
+    sign = (t < 0) & (idx > 0)
+    return (idx + 8 * sign).astype(np.uint8)
+
+
+def mx_quantize(V: np.ndarray):
+    """MXFP4 quantisation of the last axis in blocks of 32.
+
+    Per block: shared exponent se = max(floor(log2(max|v|)) - 2, -127) (2 = exponent of
+    the largest E2M1 value; 0 for an all-zero block), stored biased as E = se + 127;
+    elements e2m1_round(v / 2^se).  Division by a power of two is exact in fp32.
+    Returns (codes uint8 [..., K] with values 0..15, E uint8 [..., K/32]).
+    """
+    V = np.asarray(V, dtype=F32)
+    K = V.shape[-1]
+    assert K % MX_BLOCK == 0
+    B = V.reshape(V.shape[:-1] + (K // MX_BLOCK, MX_BLOCK))
+    amax = np.max(np.abs(B), axis=-1)
+    _, ex = np.frexp(amax)                                          # amax = m * 2^ex, m in [0.5, 1)
+    se = np.where(amax > 0, np.maximum(ex.astype(np.int32) - 1 - 2, -127), 0).astype(np.int32)
+    t = np.ldexp(B, -se[..., None]).astype(F32)
+    codes = e2m1_round(t).reshape(V.shape)
+    return codes, (se + 127).astype(np.uint8)
+
+
+def mx_dequantize(codes: np.ndarray, E: np.ndarray) -> np.ndarray:
+    """The fp64 values an MXFP4 tensor stands for: +-E2M1 value * 2^(E - 127) per block of 32."""
+    codes = np.asarray(codes)
+    mag = E2M1_VALUES.astype(np.float64)[codes & 7]
+    val = np.where(codes & 8, -mag, mag)
+    scale = np.ldexp(1.0, np.asarray(E, dtype=np.int32) - 127)
+    return val * np.repeat(scale, MX_BLOCK, axis=-1)
+
+
+def mx_pack_weights(W: np.ndarray, s, r: int, perm=None):
+    """Offline preparation for the MXFP4 path (Eq. 4, Eq. 5 with Q = MXFP4 along the input channels).
+
+      W^ = (W * s)[:, perm]                    fp32, salient channels lead
+      Wc, We = mx_quantize(W^)                 per output channel, blocks of 32 input channels
+      R[n, j] = W^[n, j] - deq(Wc, We)[n, j]   j < r, one fp32 subtraction
+      Rc, Re = mx_quantize(R)                  the compensation matrix in MXFP4 as well (Eq. 7, second line)
+    Returns dict(Wc, We, Rc, Re, perm, s_inv); Rc is [N, r] (output channel major, like Wc).
+    """
+    W = np.asarray(W, dtype=F32)
+    N, K = W.shape
+    s = np.ones(K, F32) if s is None else np.asarray(s, dtype=F32)
+    Wt = W * s[None, :]
+    perm = saliency_permutation(Wt) if perm is None else np.asarray(perm, dtype=np.int32)
+    Wp = Wt[:, perm]
+    Wc, We = mx_quantize(Wp)
+    out = {"Wc": Wc, "We": We, "perm": perm, "s_inv": (F32(1.0) / s)[perm].astype(F32)}
+    if r > 0:
+        R = (Wp[:, :r] - mx_dequantize(Wc[:, :r], We[:, :r // MX_BLOCK]).astype(F32)).astype(F32)
+        out["Rc"], out["Re"] = mx_quantize(R)
+    return out
+
+
+def mx_quantize_act(X: np.ndarray, s_inv):
+    """Online step for the MXFP4 path: flatten (Eq. 4), then MXFP4 per token in blocks of 32 channels."""
+    return mx_quantize(flatten(X, s_inv))
+
+
+def mx_linear(Xc, Xe, Wc, We, Rc=None, Re=None, s_begin: int = 0) -> np.ndarray:
+    """Y = deq(X) . deq(W)^T + deq(X)[:, S] . deq(R)^T in fp64 (Eq. 7, second line, with Q = MXFP4)."""
+    Xd = mx_dequantize(Xc, Xe)
+    Y = Xd @ mx_dequantize(Wc, We).T
+    if Rc is not None and Rc.shape[1] > 0:
+        r = Rc.shape[1]
+        Y = Y + Xd[:, s_begin:s_begin + r] @ mx_dequantize(Rc, Re).T
+    return Y
 
 
 def linear_f32(Xq, scale, Wq, wscale, R=None, s_begin: int = 0, acc=None) -> np.ndarray:

@@ -308,3 +308,99 @@ def test_q4r_reduces_to_linear_with_the_dequantised_matrix():
     bound = scale.astype(np.float64)[:, None] * (np.abs(Xq[:, :spec.r]).sum(axis=1)[:, None]
                                                  * rscale.astype(np.float64)[None, :] * 0.5)
     assert np.all(np.abs(Ya - Y16) <= bound * (1 + 1e-6) + 1e-12)
+
+
+# ---------------------------------------------------------------------------
+# MXFP4 (OCP Microscaling: E2M1 elements, E8M0 scale per block of 32)
+# ---------------------------------------------------------------------------
+def test_mx_e2m1_value_table_and_ties():
+    # the eight magnitudes of the format and every tie between neighbours (to the even mantissa bit)
+    assert orc.E2M1_VALUES.tolist() == [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0]
+    cases = {0.0: 0, 0.24: 0, 0.25: 0, 0.26: 1, 0.5: 1, 0.75: 2, 1.0: 2, 1.25: 2, 1.26: 3, 1.5: 3, 1.75: 4,
+             2.0: 4, 2.5: 4, 2.51: 5, 3.0: 5, 3.5: 6, 4.0: 6, 4.99: 6, 5.0: 6, 5.01: 7, 6.0: 7, 7.9: 7, 100.0: 7}
+    for v, code in cases.items():
+        assert orc.e2m1_round(np.float32(v)) == code, v
+        assert orc.e2m1_round(np.float32(-v)) == (code + 8 if code else 0), -v
+
+
+def test_mx_hand_worked_blocks():
+    # block 1: max 6 -> floor(log2 6) = 2 -> shared exponent 0 (E = 127); values are their own codes
+    b1 = np.array([6, -3, 1.5, 0.5, 0, 0.25, -0.75, 2.5] + [0] * 24, np.float32)
+    # block 2: max 7 -> still exponent 0; 7 saturates to 6, 5 is the tie between 4 and 6 (-> 4)
+    b2 = np.array([7, 5, -1.25] + [0] * 29, np.float32)
+    # block 3: max 0.1875 = 1.5 * 2^-3 -> floor(log2) = -3 -> exponent -5 (E = 122); 0.1875 / 2^-5 = 6
+    b3 = np.array([0.1875, -0.0625, 0.015625] + [0] * 29, np.float32)
+    # block 4: all zero -> E = 127, codes 0
+    b4 = np.zeros(32, np.float32)
+    codes, E = orc.mx_quantize(np.concatenate([b1, b2, b3, b4])[None, :])
+    assert E[0].tolist() == [127, 127, 122, 127]
+    assert codes[0, :8].tolist() == [7, 8 + 5, 3, 1, 0, 0, 8 + 2, 4]
+    assert codes[0, 32:35].tolist() == [7, 6, 8 + 2]
+    assert codes[0, 64:67].tolist() == [7, 8 + 4, 1]            # -0.0625 * 32 = -2 ; 0.015625 * 32 = 0.5
+    assert not codes[0, 96:].any()
+    d = orc.mx_dequantize(codes, E)
+    assert d[0, :8].tolist() == [6, -3, 1.5, 0.5, 0, 0, -1, 2]
+    assert d[0, 32:35].tolist() == [6, 4, -1]
+    assert d[0, 64:67].tolist() == [0.1875, -0.0625, 0.015625]
+
+
+def test_mx_power_of_two_invariance_and_error_bound():
+    rng = np.random.default_rng(11)
+    V = (rng.standard_normal((5, 256)) * np.exp(rng.standard_normal((5, 256)))).astype(np.float32)
+    codes, E = orc.mx_quantize(V)
+    for k in (-9, 3, 20):
+        c2, E2 = orc.mx_quantize(np.ldexp(V, k))
+        assert np.array_equal(c2, codes) and np.array_equal(E2.astype(int), E.astype(int) + k)
+    # inside the grid the error is at most half the local step; the block maximum may saturate (6 <- up to 8)
+    d = orc.mx_dequantize(codes, E)
+    scale = np.repeat(np.ldexp(1.0, E.astype(int) - 127), 32, axis=-1)
+    t = np.abs(V.astype(np.float64)) / scale
+    step = np.select([t < 2, t < 4, t <= 6], [0.5, 1.0, 2.0], default=4.0)
+    assert np.all(np.abs(V - d) <= 0.5 * step * scale * (1 + 1e-12))
+    assert np.all(t < 8) and np.all(np.max(t.reshape(5, 8, 32), axis=-1) >= 4)
+
+
+def test_mx_linear_is_the_matmul_of_what_the_codes_stand_for():
+    rng = np.random.default_rng(12)
+    M, K, N, r, s_begin = 3, 128, 5, 64, 32
+    # operands that are exactly representable: codes and exponents drawn directly
+    Xc, Wc, Rc = (rng.integers(0, 16, size=sh).astype(np.uint8) for sh in ((M, K), (N, K), (N, r)))
+    Xe, We, Re = (rng.integers(120, 134, size=sh).astype(np.uint8) for sh in ((M, K // 32), (N, K // 32), (N, r // 32)))
+    Y = orc.mx_linear(Xc, Xe, Wc, We, Rc, Re, s_begin=s_begin)
+    val = lambda c: (-1.0 if c & 8 else 1.0) * [0, .5, 1, 1.5, 2, 3, 4, 6][c & 7]
+    for m in range(M):
+        for n in range(N):
+            t = 0.0
+            for k in range(K):
+                t += val(Xc[m, k]) * 2.0 ** (int(Xe[m, k // 32]) - 127) * val(Wc[n, k]) * 2.0 ** (int(We[n, k // 32]) - 127)
+            for j in range(r):
+                k = s_begin + j
+                t += val(Xc[m, k]) * 2.0 ** (int(Xe[m, k // 32]) - 127) * val(Rc[n, j]) * 2.0 ** (int(Re[n, j // 32]) - 127)
+            assert abs(Y[m, n] - t) <= 1e-12 * max(1.0, abs(t))
+    # a tensor that is already on the grid survives quantisation unchanged
+    Xd = orc.mx_dequantize(Xc, Xe).astype(np.float32)
+    c2, e2 = orc.mx_quantize(Xd)
+    assert np.array_equal(orc.mx_dequantize(c2, e2), Xd.astype(np.float64))
+
+
+def test_mx_pack_residual_and_compensation():
+    spec = workloads.LayerSpec("pin", 1, 4, 6, 128, 24, 64, "bf16", "bf16", 2, 20.0, 20.0)
+    L = workloads.make_layer(spec)
+    W, s = L["W"].float().numpy(), L["s"].numpy()
+    pk = orc.mx_pack_weights(W, s, spec.r)
+    Wp = (W * s[None, :])[:, pk["perm"]]
+    Wd = orc.mx_dequantize(pk["Wc"], pk["We"])
+    Rd = orc.mx_dequantize(pk["Rc"], pk["Re"])
+    # the compensated salient rows are closer to the folded weights than the quantised ones alone
+    e0 = np.linalg.norm(Wp[:, :spec.r] - Wd[:, :spec.r])
+    e1 = np.linalg.norm(Wp[:, :spec.r] - (Wd[:, :spec.r] + Rd))
+    assert e1 < 0.5 * e0
+    # and the layer with it is closer to the unquantised product over the salient block
+    Xc, Xe = orc.mx_quantize_act(L["X"].float().numpy()[:, pk["perm"]], pk["s_inv"])
+    Xd = orc.mx_dequantize(Xc, Xe)
+    ref = Xd[:, :spec.r] @ Wp[:, :spec.r].T.astype(np.float64)
+    y0 = Xd[:, :spec.r] @ Wd[:, :spec.r].T
+    y1 = y0 + Xd[:, :spec.r] @ Rd.T
+    assert np.linalg.norm(y1 - ref) < np.linalg.norm(y0 - ref)
+    full = orc.mx_linear(Xc, Xe, pk["Wc"], pk["We"], pk["Rc"], pk["Re"])
+    assert np.allclose(full, Xd @ Wd.T + Xd[:, :spec.r] @ Rd.T, rtol=1e-12, atol=1e-12)
