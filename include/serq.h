@@ -185,6 +185,61 @@ int serq_gemm_i32(const void* Xq, int abits, const void* Wq,
                   void* workspace, size_t workspace_bytes, int flags, void* stream);
 
 /*
+ * ---- MXFP4 variant of the layer ------------------------------------------------------------------
+ * The paper's W4A4 latency runs use the 4-bit Microscaling format (Sec. 4.1 and the appendix on MXFP4
+ * kernels); arithmetic per the OCP Microscaling specification: blocks of 32 consecutive (permuted)
+ * input channels share one scale 2^(E-127), E = 127 + max(floor(log2(max|v|)) - 2, -127) (E = 127 for
+ * an all-zero block), elements are E2M1 codes (bit 3 = sign, bits 0..2 index 0, 0.5, 1, 1.5, 2, 3, 4,
+ * 6), round to nearest, ties to the code with an even mantissa bit, larger magnitudes saturate at 6.
+ * Weights, activations and the compensation matrix (along its rank index) all take this form (Eq. 7,
+ * second line, with Q = MXFP4), so the layer is
+ *   Y[m,n] = sum_k X^[m,k] W^[n,k] + sum_{j<r} X^[m,s_begin+j] R^[n,j]
+ * with no further scales.  It runs on the block-scaled FP4 matrix instructions; there is no decode
+ * (skinny) variant of it.
+ *
+ * Buffers (device memory, 16-byte aligned; opaque except through the unpack calls):
+ *   activation codes  serq_packed_act_bytes(M,K,4) bytes
+ *   activation scales serq_mx_act_scale_bytes(M,K) bytes
+ *   weight codes      serq_packed_weight_bytes(N,K) bytes
+ *   weight scales     serq_mx_weight_scale_bytes(N,K) bytes
+ *   compensation      codes serq_packed_weight_bytes(N, 64*ceil(r/64)), scales
+ *                     serq_mx_weight_scale_bytes(N, 64*ceil(r/64)) (ranks past r are zero)
+ */
+size_t serq_mx_act_scale_bytes(int64_t M, int64_t K);
+size_t serq_mx_weight_scale_bytes(int64_t N, int64_t K);
+
+/* Online step 1 for the MXFP4 layer: flattening (Eq. 4; s_inv may be NULL) and MXFP4 quantisation of
+ * each token in blocks of 32 channels.  X [M,K] fp16/bf16/fp32, row stride ldx (multiple of 8). */
+int serq_mx_quantize_act(const void* X, int x_dtype, const float* s_inv, int64_t M, int64_t K, int64_t ldx,
+                         void* Xq_out, uint8_t* xscale_out, void* stream);
+
+/* Offline preparation for the MXFP4 layer (Sec. 3.2 with Q = MXFP4): W~ = (W * s)[:, perm] in fp32
+ * (s, perm_in, perm_out, s_inv_out as in serq_pack_weights), MXFP4 per output channel in blocks of 32
+ * input channels; R[n,j] = W~[n,j] - dequantised W~[n,j] for the r leading channels (one fp32
+ * subtraction), itself in MXFP4 in blocks of 32 ranks.  r is a multiple of 32 (0: Rq_out / rscale_out
+ * ignored). */
+int serq_mx_pack_weights(const void* W, int w_dtype, const float* s, const int32_t* perm_in,
+                         int64_t N, int64_t K, int r,
+                         void* Wq_out, uint8_t* wscale_out, int32_t* perm_out, float* s_inv_out,
+                         void* Rq_out, uint8_t* rscale_out, void* stream);
+
+/* Canonical views (parity checks): codes uint8 [rows,K] (0..15), exponent bytes uint8 [rows,K/32].
+ * A packed compensation matrix is viewed with serq_mx_unpack_weights(Rq, rscale, N, 64*ceil(r/64)). */
+int serq_mx_unpack_weights(const void* Wq, const uint8_t* wscale, int64_t N, int64_t K,
+                           uint8_t* codes_out, uint8_t* exps_out, void* stream);
+int serq_mx_unpack_act(const void* Xq, const uint8_t* xscale, int64_t M, int64_t K,
+                       uint8_t* codes_out, uint8_t* exps_out, void* stream);
+
+/* The MXFP4 layer.  Y [M,N] in y_dtype, row stride ldy (multiple of 8, >= N); fp32 accumulation over
+ * k in the order of the hardware's 64-channel steps, the compensation sum added to the same
+ * accumulators.  s_begin is a multiple of 256 with s_begin + 64*ceil(r/64) <= K; r a multiple of 32;
+ * Rq may be NULL (no compensation).  flags: SERQ_FLAG_COLTILES only.  M = 0 is a no-op. */
+int serq_mx_linear(const void* Xq, const uint8_t* xscale, const void* Wq, const uint8_t* wscale,
+                   int s_begin, int r, const void* Rq, const uint8_t* rscale,
+                   int64_t M, int64_t N, int64_t K,
+                   void* Y, int y_dtype, int64_t ldy, int flags, void* stream);
+
+/*
  * Measuring sticks for benchmarks (no part of the layer; see the roofline discussion of Sec. 4.3's
  * latency tables only in so far as they say what "peak" means on this part).
  *

@@ -44,6 +44,13 @@ SIGNATURES = {
     "serq_linear": (_i, [_vp, _vp, _i, _vp, _vp, _i, _i, _vp, _i, _i64, _i64, _i64, _vp, _i, _i64,
                          _vp, _sz, _i, _vp]),
     "serq_gemm_i32": (_i, [_vp, _i, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _sz, _i, _vp]),
+    "serq_mx_act_scale_bytes": (_sz, [_i64, _i64]),
+    "serq_mx_weight_scale_bytes": (_sz, [_i64, _i64]),
+    "serq_mx_quantize_act": (_i, [_vp, _i, _vp, _i64, _i64, _i64, _vp, _vp, _vp]),
+    "serq_mx_pack_weights": (_i, [_vp, _i, _vp, _vp, _i64, _i64, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "serq_mx_unpack_weights": (_i, [_vp, _vp, _i64, _i64, _vp, _vp, _vp]),
+    "serq_mx_unpack_act": (_i, [_vp, _vp, _i64, _i64, _vp, _vp, _vp]),
+    "serq_mx_linear": (_i, [_vp, _vp, _vp, _vp, _i, _i, _vp, _vp, _i64, _i64, _i64, _vp, _i, _i64, _i, _vp]),
     "serq_bench_mfma_peak": (_i, [_vp, _i, _i, _vp, _vp]),
     "serq_bench_read": (_i, [_vp, _sz, _i, _vp, _vp]),
 }
@@ -236,6 +243,98 @@ def gemm_i32(Xq: torch.Tensor, abits: int, Wq: torch.Tensor, M: int, N: int, K: 
                              _ptr(ws), 0 if ws is None else ws.numel(), flags_, _stream())
     _check("serq_gemm_i32", rc)
     return acc
+
+
+# ---- MXFP4 variant ---------------------------------------------------------------------------------
+@dataclass
+class MxPackedLayer:
+    """Device-resident artefacts of serq_mx_pack_weights for one layer."""
+    N: int
+    K: int
+    r: int
+    Wq: torch.Tensor        # uint8 blob: E2M1 codes
+    wsc: torch.Tensor       # uint8 blob: E8M0 block scales
+    perm: torch.Tensor      # int32 [K]
+    s_inv: torch.Tensor     # fp32 [K]
+    Rq: Optional[torch.Tensor]
+    rsc: Optional[torch.Tensor]
+
+
+def mx_pack_weights(W: torch.Tensor, s: Optional[torch.Tensor], r: int,
+                    perm_in: Optional[torch.Tensor] = None) -> MxPackedLayer:
+    _dev(W, "W")
+    N, K = W.shape
+    L = lib()
+    nbytes = L.serq_packed_weight_bytes(N, K)
+    if nbytes == 0:
+        raise SerqError("serq_packed_weight_bytes", -3)
+    dev = W.device
+    Wq = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    wsc = torch.empty(L.serq_mx_weight_scale_bytes(N, K), dtype=torch.uint8, device=dev)
+    perm = torch.empty(K, dtype=torch.int32, device=dev)
+    s_inv = torch.empty(K, dtype=torch.float32, device=dev)
+    Rq = rsc = None
+    if r > 0:
+        rk = 64 * ((r + 63) // 64)
+        Rq = torch.empty(max(L.serq_packed_weight_bytes(N, rk), 16), dtype=torch.uint8, device=dev)
+        rsc = torch.empty(max(L.serq_mx_weight_scale_bytes(N, rk), 16), dtype=torch.uint8, device=dev)
+    if s is not None:
+        _dev(s, "s")
+    if perm_in is not None:
+        _dev(perm_in, "perm_in")
+    rc = L.serq_mx_pack_weights(_ptr(W), _DT[W.dtype], _ptr(s), _ptr(perm_in), N, K, r, _ptr(Wq), _ptr(wsc),
+                                _ptr(perm), _ptr(s_inv), _ptr(Rq), _ptr(rsc), _stream())
+    _check("serq_mx_pack_weights", rc)
+    return MxPackedLayer(N, K, r, Wq, wsc, perm, s_inv, Rq, rsc)
+
+
+def mx_unpack_weights(Wq: torch.Tensor, wsc: torch.Tensor, N: int, K: int):
+    """Canonical view: (codes uint8 [N,K], exponent bytes uint8 [N,K/32])."""
+    codes = torch.empty((N, K), dtype=torch.uint8, device=Wq.device)
+    exps = torch.empty((N, K // 32), dtype=torch.uint8, device=Wq.device)
+    _check("serq_mx_unpack_weights",
+           lib().serq_mx_unpack_weights(_ptr(Wq), _ptr(wsc), N, K, _ptr(codes), _ptr(exps), _stream()))
+    return codes, exps
+
+
+def mx_quantize_act(X: torch.Tensor, s_inv: Optional[torch.Tensor],
+                    Xq: Optional[torch.Tensor] = None, xsc: Optional[torch.Tensor] = None):
+    """serq_mx_quantize_act: returns (E2M1 codes blob, E8M0 block-scale blob)."""
+    if not X.is_cuda:
+        raise ValueError("X must live in device memory")
+    if X.dim() != 2 or X.stride(1) != 1:
+        raise ValueError("X must be [M,K] with unit inner stride")
+    M, K = X.shape
+    L = lib()
+    if Xq is None:
+        Xq = torch.empty(max(L.serq_packed_act_bytes(M, K, 4), 16), dtype=torch.uint8, device=X.device)
+    if xsc is None:
+        xsc = torch.empty(max(L.serq_mx_act_scale_bytes(M, K), 16), dtype=torch.uint8, device=X.device)
+    ldx = X.stride(0) if M > 0 else K
+    rc = L.serq_mx_quantize_act(_ptr(X), _DT[X.dtype], _ptr(s_inv), M, K, ldx, _ptr(Xq), _ptr(xsc), _stream())
+    _check("serq_mx_quantize_act", rc)
+    return Xq, xsc
+
+
+def mx_unpack_act(Xq: torch.Tensor, xsc: torch.Tensor, M: int, K: int):
+    codes = torch.empty((M, K), dtype=torch.uint8, device=Xq.device)
+    exps = torch.empty((M, K // 32), dtype=torch.uint8, device=Xq.device)
+    _check("serq_mx_unpack_act",
+           lib().serq_mx_unpack_act(_ptr(Xq), _ptr(xsc), M, K, _ptr(codes), _ptr(exps), _stream()))
+    return codes, exps
+
+
+def mx_linear(Xq: torch.Tensor, xsc: torch.Tensor, Wq: torch.Tensor, wsc: torch.Tensor, M: int, N: int, K: int,
+              Rq: Optional[torch.Tensor] = None, rsc: Optional[torch.Tensor] = None, r: int = 0, s_begin: int = 0,
+              out_dtype: torch.dtype = torch.bfloat16, Y: Optional[torch.Tensor] = None,
+              flags_: int = 0) -> torch.Tensor:
+    """serq_mx_linear: Y = deq(X) . deq(W)^T + deq(X)[:, S] . deq(R)^T on the block-scaled FP4 units."""
+    if Y is None:
+        Y = torch.empty((M, N), dtype=out_dtype, device=Xq.device)
+    rc = lib().serq_mx_linear(_ptr(Xq), _ptr(xsc), _ptr(Wq), _ptr(wsc), s_begin, r, _ptr(Rq), _ptr(rsc), M, N, K,
+                              _ptr(Y), _DT[Y.dtype], Y.stride(0) if M > 0 else N, flags_, _stream())
+    _check("serq_mx_linear", rc)
+    return Y
 
 
 def bench_mfma_peak(operands: torch.Tensor, iters: int, workgroups: int, sink: torch.Tensor) -> None:

@@ -231,6 +231,92 @@ int serq_gemm_i32(const void* Xq, int abits, const void* Wq,
   return linear_common(a, M, N, K, flags, stream);
 }
 
+// ---- MXFP4 path -------------------------------------------------------------------------------------
+size_t serq_mx_act_scale_bytes(int64_t M, int64_t K) {
+  if (M < 0 || K < 64 || K > 131072 || (K % 64) != 0) return 0;
+  return (size_t)((K + 255) / 256) * (size_t)((M + 1) & ~(int64_t)1) * 8;
+}
+
+size_t serq_mx_weight_scale_bytes(int64_t N, int64_t K) {
+  if (N < 32 || (N % 32) != 0 || N > (1 << 24) || K < 64 || K > 131072 || (K % 64) != 0) return 0;
+  return (size_t)(N / 32) * (size_t)((K + 255) / 256) * 256;
+}
+
+int serq_mx_quantize_act(const void* X, int x_dtype, const float* s_inv, int64_t M, int64_t K, int64_t ldx,
+                         void* Xq_out, uint8_t* xscale_out, void* stream) {
+  if (!dtype_ok(x_dtype)) return SERQ_EDTYPE;
+  if (M < 0 || M > 0x7fffffff || K < 64 || K > 131072 || (K % 64) != 0) return SERQ_ESHAPE;
+  if (ldx < K) return SERQ_ESHAPE;
+  if ((ldx % 8) != 0) return SERQ_EALIGN;
+  if (M == 0) return SERQ_OK;
+  if (!X || !Xq_out || !xscale_out) return SERQ_ENULL;
+  if (!aligned16(X) || !aligned16(Xq_out) || !aligned16(s_inv) || !aligned16(xscale_out)) return SERQ_EALIGN;
+  return launch_mx_quantize_act(X, x_dtype, s_inv, M, (int)K, ldx, Xq_out, xscale_out, (hipStream_t)stream);
+}
+
+int serq_mx_pack_weights(const void* W, int w_dtype, const float* s, const int32_t* perm_in,
+                         int64_t N, int64_t K, int r,
+                         void* Wq_out, uint8_t* wscale_out, int32_t* perm_out, float* s_inv_out,
+                         void* Rq_out, uint8_t* rscale_out, void* stream) {
+  if (!W || !Wq_out || !wscale_out || !perm_out || !s_inv_out) return SERQ_ENULL;
+  if (!dtype_ok(w_dtype)) return SERQ_EDTYPE;
+  int rc = check_nk(N, K);
+  if (rc != SERQ_OK) return rc;
+  if (r < 0 || (r % 32) != 0 || r > K) return SERQ_ESHAPE;
+  if (r > 0 && (!Rq_out || !rscale_out)) return SERQ_ENULL;
+  if (!aligned16(W) || !aligned16(Wq_out) || !aligned16(wscale_out) || !aligned16(perm_out) ||
+      !aligned16(s_inv_out) || !aligned16(Rq_out) || !aligned16(rscale_out) || !aligned16(s) || !aligned16(perm_in))
+    return SERQ_EALIGN;
+  rc = prepare_perm_impl(W, w_dtype, s, perm_in, (int)N, (int)K, perm_out, s_inv_out, (hipStream_t)stream);
+  if (rc != SERQ_OK) return rc;
+  return mx_pack_weights_impl(W, w_dtype, s, perm_out, (int)N, (int)K, r, Wq_out, wscale_out, Rq_out, rscale_out,
+                              (hipStream_t)stream);
+}
+
+int serq_mx_unpack_weights(const void* Wq, const uint8_t* wscale, int64_t N, int64_t K,
+                           uint8_t* codes_out, uint8_t* exps_out, void* stream) {
+  if (!Wq || !wscale || !codes_out || !exps_out) return SERQ_ENULL;
+  const int rc = check_nk(N, K);
+  if (rc != SERQ_OK) return rc;
+  if (!aligned16(Wq) || !aligned16(wscale)) return SERQ_EALIGN;
+  return mx_unpack_weights_impl(Wq, wscale, (int)N, (int)K, codes_out, exps_out, (hipStream_t)stream);
+}
+
+int serq_mx_unpack_act(const void* Xq, const uint8_t* xscale, int64_t M, int64_t K,
+                       uint8_t* codes_out, uint8_t* exps_out, void* stream) {
+  if (M < 0 || M > 0x7fffffff || K < 64 || K > 131072 || (K % 64) != 0) return SERQ_ESHAPE;
+  if (M == 0) return SERQ_OK;
+  if (!Xq || !xscale || !codes_out || !exps_out) return SERQ_ENULL;
+  if (!aligned16(Xq) || !aligned16(xscale)) return SERQ_EALIGN;
+  return mx_unpack_act_impl(Xq, xscale, M, (int)K, codes_out, exps_out, (hipStream_t)stream);
+}
+
+int serq_mx_linear(const void* Xq, const uint8_t* xscale, const void* Wq, const uint8_t* wscale,
+                   int s_begin, int r, const void* Rq, const uint8_t* rscale,
+                   int64_t M, int64_t N, int64_t K,
+                   void* Y, int y_dtype, int64_t ldy, int flags, void* stream) {
+  int rc = check_nk(N, K);
+  if (rc != SERQ_OK) return rc;
+  if (M < 0 || M > (1 << 24)) return SERQ_ESHAPE;
+  if (!dtype_ok(y_dtype)) return SERQ_EDTYPE;
+  if (r < 0 || (r % 32) != 0 || s_begin < 0 || (s_begin % 256) != 0) return SERQ_ESHAPE;
+  if (r > 0 && Rq && (int64_t)s_begin + 64 * ((r + 63) / 64) > K) return SERQ_ESHAPE;
+  if (ldy < N) return SERQ_ESHAPE;
+  if (M == 0) return SERQ_OK;
+  if (!Xq || !xscale || !Wq || !wscale || !Y) return SERQ_ENULL;
+  if (r > 0 && Rq && !rscale) return SERQ_ENULL;
+  if ((ldy % 8) != 0 || !aligned16(Y) || !aligned16(Xq) || !aligned16(xscale) || !aligned16(Wq) ||
+      !aligned16(wscale) || !aligned16(Rq) || !aligned16(rscale))
+    return SERQ_EALIGN;
+  MxLinearArgs a{};
+  a.Xq = (const uint8_t*)Xq; a.xsc = xscale; a.Wq = (const u4*)Wq; a.wsc = wscale;
+  a.s_begin = s_begin; a.r = (Rq ? r : 0); a.Rq = (r > 0 ? (const u4*)Rq : nullptr); a.rsc = rscale;
+  a.M = (int)M; a.N = (int)N; a.K = (int)K;
+  a.Y = Y; a.y_dtype = y_dtype; a.ldy = ldy;
+  a.coltiles = (flags >> 20) & 0x7ff;
+  return launch_mx_linear(a, (hipStream_t)stream);
+}
+
 int serq_bench_mfma_peak(const void* operands, int iters, int workgroups, void* sink, void* stream) {
   if (!operands || !sink) return SERQ_ENULL;
   if (iters < 0 || workgroups <= 0 || workgroups > (1 << 20)) return SERQ_ESHAPE;

@@ -43,6 +43,7 @@
 // row segments.
 #include <type_traits>
 
+#include "gemm_tile.h"
 #include "serq_device.h"
 
 namespace serq {
@@ -88,42 +89,6 @@ struct MfmaParams {
   int tiles_m, tiles_n, groupm;
   int wide, nwide;        // column tiles 0..nwide-1 have `wide` blocks of 32 channels, the rest wide-1
 };
-
-// Workgroup id -> output tile.  Consecutive ids go to different XCDs (8 of
-// them, each with its own L2), so ids are first regrouped into one contiguous
-// range per XCD; inside a range, tiles are ordered in bands of `groupm` token
-// tiles so that the tiles in flight on one XCD share weight and token panels.
-__device__ __forceinline__ void map_block(int bid, int tm, int tn, int gm, int& tile_m, int& tile_n) {
-  const int T = tm * tn;
-  const int per = (T + 7) >> 3;
-  const int tall = (T & 7) == 0 ? 8 : (T & 7);
-  const int xcd = bid & 7, loc = bid >> 3;
-  const int logical = xcd < tall ? xcd * per + loc : tall * per + (xcd - tall) * (per - 1) + loc;
-  const int gsize = gm * tn;
-  const int grp = logical / gsize;
-  const int first_m = grp * gm;
-  const int gsz = (tm - first_m) < gm ? (tm - first_m) : gm;
-  const int within = logical - grp * gsize;
-  tile_m = first_m + within % gsz;
-  tile_n = within / gsz;
-}
-
-// ---- direct-to-LDS loads and the hand-counted waits --------------------------
-__device__ __forceinline__ uint32_t lds_addr(const void* ptr) {
-  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)ptr;
-}
-// 16 bytes per lane: global (sbase + voff) -> LDS (lds_base_uniform + 16 * lane)
-__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base_uniform) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds_base_uniform), "v"(voff), "s"(sbase) : "memory", "m0");
-}
-// all but the youngest N vector-memory operations of this wave have completed,
-// this wave's LDS reads are complete, and every wave of the workgroup has got here
-template <int N>
-__device__ __forceinline__ void wait_dma_barrier() {
-  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" :: "n"(N) : "memory");
-}
-__device__ __forceinline__ void fence() { __builtin_amdgcn_sched_barrier(0); }
 
 // ---- operand fragments ---------------------------------------------------------
 template <int ABITS>
@@ -698,31 +663,6 @@ void serq_mfma_kernel(const MfmaParams p) {
     case 2: body(std::integral_constant<int, 2>{}); break;
     default: body(std::integral_constant<int, 1>{}); break;   // a wave without blocks computes a duplicate it never stores
   }
-}
-
-// Column tiling: C tiles of `wide` or wide-1 blocks of 32 channels.  Estimated time of a launch:
-// tiles are dealt to the compute units round by round, a round costs as much as its widest tile,
-// and a tile of b blocks costs b + kFixed (the token panel and the per-step overheads do not
-// shrink with the tile).
-void plan_columns(int tiles_m, int NB, int ncu, int& C_out, int& wide_out, int& nwide_out) {
-  const float kFixed = 4.0f;
-  float best = 0.0f;
-  int bestC = 0;
-  const int cmin = (NB + 7) / 8;
-  for (int C = cmin; C <= NB; ++C) {
-    const int wide = (NB + C - 1) / C;
-    const int nwide = NB - C * (wide - 1);            // tiles with `wide` blocks (the first ones)
-    const long long tiles = (long long)tiles_m * C;
-    const long long wide_tiles = (long long)tiles_m * nwide;
-    const long long rounds = (tiles + ncu - 1) / ncu;
-    const long long wide_rounds = (wide_tiles + ncu - 1) / ncu;
-    const float cost = wide_rounds * (wide + kFixed) + (rounds - wide_rounds) * (wide - 1 + kFixed);
-    if (bestC == 0 || cost < best - 1e-6f) { best = cost; bestC = C; }
-    if (wide <= 2) break;                             // narrower tiles only add overhead
-  }
-  C_out = bestC;
-  wide_out = (NB + bestC - 1) / bestC;
-  nwide_out = NB - bestC * (wide_out - 1);
 }
 
 }  // namespace

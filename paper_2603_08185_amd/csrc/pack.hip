@@ -281,6 +281,20 @@ int pack_weights_impl(const void* W, int w_dtype, const float* s, const int32_t*
   return ok();
 }
 
+// saliency order (or the caller's) and the reciprocal flattening vector in that order
+int prepare_perm_impl(const void* W, int w_dtype, const float* s, const int32_t* perm_in, int N, int K,
+                      int32_t* perm_out, float* s_inv_out, hipStream_t st) {
+  if (perm_in) {
+    hipLaunchKernelGGL(copy_perm_kernel, dim3(blocks_for(K)), dim3(kT), 0, st, perm_in, K, perm_out);
+  } else {
+    float* sal = s_inv_out;  // borrowed until sinv_kernel overwrites it
+    hipLaunchKernelGGL(col_saliency_kernel, dim3(blocks_for(K)), dim3(kT), 0, st, W, w_dtype, s, N, K, sal);
+    hipLaunchKernelGGL(rank_perm_kernel, dim3(blocks_for(K)), dim3(kT), 0, st, sal, K, perm_out);
+  }
+  hipLaunchKernelGGL(sinv_kernel, dim3(blocks_for(K)), dim3(kT), 0, st, s, perm_out, K, s_inv_out);
+  return ok();
+}
+
 int pack_lowrank_impl(void* R, int N, int r, void* Rp, bool unpack, hipStream_t st) {
   if (r == 0) return SERQ_OK;
   hipLaunchKernelGGL(pack_lowrank_kernel, dim3(blocks_for((size_t)r * N)), dim3(kT), 0, st, (uint16_t*)R, N, r,

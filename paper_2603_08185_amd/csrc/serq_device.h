@@ -9,6 +9,7 @@
 namespace serq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -171,9 +172,28 @@ int launch_quantize_act(const void* X, int x_dtype, const float* s_inv, int64_t 
 int launch_mfma_peak(const void* operands, int iters, int workgroups, void* sink, hipStream_t st);
 int launch_read_peak(const void* src, size_t bytes, int workgroups, void* sink, hipStream_t st);
 
+// MXFP4 path (mx.hip, gemm_mx.hip)
+struct MxLinearArgs {
+  const uint8_t* Xq; const uint8_t* xsc;
+  const u4* Wq; const uint8_t* wsc;
+  int s_begin; int r; const u4* Rq; const uint8_t* rsc;
+  int M, N, K;
+  void* Y; int y_dtype; int64_t ldy;
+  int coltiles;
+};
+int launch_mx_quantize_act(const void* X, int x_dtype, const float* s_inv, int64_t M, int K, int64_t ldx, void* Xq,
+                           uint8_t* xsc, hipStream_t st);
+int mx_pack_weights_impl(const void* W, int w_dtype, const float* s, const int32_t* perm, int N, int K, int r,
+                         void* Wq, uint8_t* wsc, void* Rq, uint8_t* rsc, hipStream_t st);
+int mx_unpack_weights_impl(const void* Wq, const uint8_t* wsc, int N, int K, uint8_t* codes, uint8_t* E, hipStream_t st);
+int mx_unpack_act_impl(const void* Xq, const uint8_t* xsc, int64_t M, int K, uint8_t* codes, uint8_t* E, hipStream_t st);
+int launch_mx_linear(const MxLinearArgs& a, hipStream_t st);
+
 int pack_weights_impl(const void* W, int w_dtype, const float* s, const int32_t* perm_in, int N, int K, int r,
                       void* Wq_out, float* wscale_out, int32_t* perm_out, float* s_inv_out, void* R_out,
                       int r_dtype, void* Rp_out, hipStream_t st);
+int prepare_perm_impl(const void* W, int w_dtype, const float* s, const int32_t* perm_in, int N, int K,
+                      int32_t* perm_out, float* s_inv_out, hipStream_t st);
 int pack_lowrank_impl(void* R, int N, int r, void* Rp, bool unpack, hipStream_t st);
 size_t lowrank_q4_frag_bytes(int N, int r);
 int pack_lowrank_q4_impl(const void* R, int r_dtype, int N, int r, void* Rq, hipStream_t st);
