@@ -46,6 +46,7 @@ sys.path.insert(0, ROOT)
 import workloads  # noqa: E402
 from paper_2603_08185_amd import binding as serq  # noqa: E402
 
+FP4_PEAK_TFLOPS = 10100.0  # dense FP4 MFMA, MI355X datasheet
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, 5.0 POP/s
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, 8 TB/s
 
@@ -113,6 +114,71 @@ def bench_prefill(steps: int, warmup: int):
         "tops_linear": ops / (l_ms * 1e-3) / 1e12,
         "quant_gbs": qbytes / (q_ms * 1e-3) / 1e9,
         "layer": (L, pk), "Xq": Xq,
+    }
+
+
+def bench_mx(steps: int, warmup: int, which: str = "up"):
+    """The MXFP4 variant of the layer on the headline shape: one JSON line of its own (`--mx`)."""
+    spec = workloads.config3(which, 4096)
+    L = workloads.make_layer(spec, want=("X", "s", "W"))
+    dev = "cuda:0"
+    pk = serq.mx_pack_weights(L["W"].to(dev), L["s"].to(dev), spec.r)
+    Xhat = workloads.permute_channels(L["X"], pk.perm.cpu().numpy()).to(dev)
+    M, N, K, r = spec.M, spec.N, spec.K, spec.r
+    Xq = torch.empty(M * K // 2, dtype=torch.uint8, device=dev)
+    xsc = torch.empty(serq.lib().serq_mx_act_scale_bytes(M, K), dtype=torch.uint8, device=dev)
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+
+    def quant():
+        serq.mx_quantize_act(Xhat, pk.s_inv, Xq=Xq, xsc=xsc)
+
+    def lin():
+        serq.mx_linear(Xq, xsc, pk.Wq, pk.wsc, M, N, K, Rq=pk.Rq, rsc=pk.rsc, r=r, Y=Y)
+
+    def step():
+        quant()
+        lin()
+
+    spin_up(step)
+    for _ in range(warmup):
+        step()
+    ev = _events(2 * steps + 1)
+    torch.cuda.synchronize()
+    ev[0].record()
+    for i in range(steps):
+        quant()
+        ev[2 * i + 1].record()
+        lin()
+        ev[2 * i + 2].record()
+    torch.cuda.synchronize()
+    total_ms = ev[0].elapsed_time(ev[-1])
+    q_ms = float(np.mean([ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(steps)]))
+    l_ms = float(np.mean([ev[2 * i + 1].elapsed_time(ev[2 * i + 2]) for i in range(steps)]))
+    ops = 2.0 * M * N * K
+    qbytes = 2.0 * M * K + M * K / 2 + M * K / 32
+    tf_lin = ops / (l_ms * 1e-3) / 1e12
+    # what the part sustains on nothing but FP4 MFMAs fed with this layer's own code bytes
+    ops_buf = torch.cat([pk.Wq[:16384].reshape(256, 4, 16), Xq[:16384].reshape(256, 4, 16)], dim=1).contiguous()
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    iters, wgs = 2000, 1024
+    run = lambda: serq.bench_mfma_fp4_peak(ops_buf, iters, wgs, sink)
+    spin_up(run, 0.1)
+    fp4_tf = 2.0 * 32 * 32 * 64 * 16 * iters * 4 * wgs / _time_launches(lambda i: run(), 5) / 1e6
+    return {
+        "variant": "mxfp4", "metric": "fused SERQ linear in MXFP4, TFLOP/s (M=4096), 1 MI355X",
+        "value": round(ops / (total_ms / steps * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": round(total_ms / steps, 5), "higher_is_better": True,
+        "dtype": "fp4 (E2M1 x E8M0 block scales), fp32 accumulation", "data": "synthetic",
+        "config": {"workload": f"configs[2]: MLP {which} projection in MXFP4 (weights, activations, compensation "
+                               "matrix), M=4096, bf16 in/out; step = serq_mx_quantize_act + serq_mx_linear",
+                   "M": M, "K": K, "N": N, "r": r},
+        "roofline": {"bound": "mfma", "kernel": "serq_mx_kernel (serq_mx_linear)", "achieved": round(tf_lin, 2),
+                     "peak": FP4_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tf_lin / FP4_PEAK_TFLOPS, 4),
+                     "traffic": None, "kernel_ms": round(l_ms, 5),
+                     "frac_of_measured_mfma_peak": round(tf_lin / fp4_tf, 4)},
+        "measured_peaks": {"mfma_fp4_tflops": round(fp4_tf, 1), "mfma_operands": "this layer's codes"},
+        "quantize_act": {"ms": round(q_ms, 5), "gbs": round(qbytes / (q_ms * 1e-3) / 1e9, 1),
+                         "frac_hbm_peak": round(qbytes / (q_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
     }
 
 
@@ -323,6 +389,27 @@ def sweep():
             ops = 2.0 * M * N * K
             row.update({"bound": "mfma", "tops": round(ops / l_us / 1e6, 1),
                         "frac": round(ops / l_us / 1e6 / INT8_PEAK_TOPS, 4)})
+            # the same layer in MXFP4 (weights, activations and compensation matrix), on the FP4 units
+            rm = 32 * (r // 32)
+            Lw = workloads.make_layer(spec, want=("s", "W"))
+            mpk = serq.mx_pack_weights(Lw["W"].to(dev), Lw["s"].to(dev), rm, perm_in=pk.perm)
+            del Lw
+            xsc = torch.empty(max(serq.lib().serq_mx_act_scale_bytes(M, K), 16), dtype=torch.uint8, device=dev)
+            Xq4 = torch.empty(M * K // 2, dtype=torch.uint8, device=dev)
+
+            def mq(i):
+                serq.mx_quantize_act(Xhat, mpk.s_inv, Xq=Xq4, xsc=xsc)
+
+            def mlin(i):
+                serq.mx_linear(Xq4, xsc, mpk.Wq, mpk.wsc, M, N, K, Rq=mpk.Rq, rsc=mpk.rsc, r=rm, Y=Y)
+
+            mq(0)
+            spin_up(lambda: mlin(0), 0.05)
+            mq_us = _time_launches(mq, n)
+            ml_us = _time_launches(mlin, n)
+            row["mxfp4"] = {"r": rm, "quantize_act_us": round(mq_us, 2), "serq_mx_linear_us": round(ml_us, 2),
+                            "tflops": round(ops / ml_us / 1e6, 1), "frac_of_fp4_peak": round(ops / ml_us / 1e6 / FP4_PEAK_TFLOPS, 4)}
+            del mpk
         print(json.dumps(row), flush=True)
         del Wqs, Rps, Rqs
 
@@ -344,6 +431,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the M=1 decode leg")
     ap.add_argument("--calibrate-copy", action="store_true", help="only run a plain 1 GiB device copy (counter calibration)")
+    ap.add_argument("--mx", nargs="?", const="up", default=None, choices=["up", "down"],
+                    help="time the MXFP4 variant of the layer on the headline shape (up, default) or its down projection instead")
     ap.add_argument("--sweep", action="store_true", help="time every benchmark configuration (one JSON line per row) instead of the headline step")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -358,6 +447,9 @@ def main():
         return
     if a.sweep:
         sweep()
+        return
+    if a.mx:
+        print(json.dumps(bench_mx(a.steps, a.warmup, a.mx)))
         return
 
     pre = bench_prefill(a.steps, a.warmup)

@@ -247,11 +247,15 @@ int serq_mx_linear(const void* Xq, const uint8_t* xscale, const void* Wq, const 
  *   held in registers: 2 * 32*32*32 * 16 * iters * 4 * workgroups integer operations and nothing else.
  *   operands: 32 KiB (256 threads x 8 x 16 bytes: 4 A and 4 B operand registers per thread), device memory;
  *   the achieved rate depends on these bytes.  sink: 4 bytes of device memory (never written in practice).
+ * serq_bench_mfma_fp4_peak: the same loop with the block-scaled FP4 MFMA (32x32x64, E2M1 codes, block
+ *   exponent 127): 2 * 32*32*64 * 16 * iters * 4 * workgroups operations.  Each 16-byte operand slot holds
+ *   the 32 codes of one lane.
  * serq_bench_read: reads [src, src + bytes) once with 16-byte loads from `workgroups` workgroups and
  *   does nothing else.  bytes a multiple of 16.
- * Both return SERQ_OK or a negative code; both only launch (asynchronous on `stream`).
+ * All return SERQ_OK or a negative code; all only launch (asynchronous on `stream`).
  */
 int serq_bench_mfma_peak(const void* operands, int iters, int workgroups, void* sink, void* stream);
+int serq_bench_mfma_fp4_peak(const void* operands, int iters, int workgroups, void* sink, void* stream);
 int serq_bench_read(const void* src, size_t bytes, int workgroups, void* sink, void* stream);
 
 #ifdef __cplusplus

@@ -52,6 +52,7 @@ SIGNATURES = {
     "serq_mx_unpack_act": (_i, [_vp, _vp, _i64, _i64, _vp, _vp, _vp]),
     "serq_mx_linear": (_i, [_vp, _vp, _vp, _vp, _i, _i, _vp, _vp, _i64, _i64, _i64, _vp, _i, _i64, _i, _vp]),
     "serq_bench_mfma_peak": (_i, [_vp, _i, _i, _vp, _vp]),
+    "serq_bench_mfma_fp4_peak": (_i, [_vp, _i, _i, _vp, _vp]),
     "serq_bench_read": (_i, [_vp, _sz, _i, _vp, _vp]),
 }
 
@@ -341,6 +342,13 @@ def bench_mfma_peak(operands: torch.Tensor, iters: int, workgroups: int, sink: t
     """serq_bench_mfma_peak: nothing but int8 MFMAs on the given 32 KiB of operand bytes."""
     assert operands.numel() * operands.element_size() >= 32768
     _check("serq_bench_mfma_peak", lib().serq_bench_mfma_peak(_ptr(operands), iters, workgroups, _ptr(sink), _stream()))
+
+
+def bench_mfma_fp4_peak(operands: torch.Tensor, iters: int, workgroups: int, sink: torch.Tensor) -> None:
+    """serq_bench_mfma_fp4_peak: nothing but block-scaled FP4 MFMAs on the given 32 KiB of operand bytes."""
+    assert operands.numel() * operands.element_size() >= 32768
+    _check("serq_bench_mfma_fp4_peak",
+           lib().serq_bench_mfma_fp4_peak(_ptr(operands), iters, workgroups, _ptr(sink), _stream()))
 
 
 def bench_read(src: torch.Tensor, nbytes: int, workgroups: int, sink: torch.Tensor) -> None:

@@ -324,6 +324,13 @@ int serq_bench_mfma_peak(const void* operands, int iters, int workgroups, void* 
   return launch_mfma_peak(operands, iters, workgroups, sink, (hipStream_t)stream);
 }
 
+int serq_bench_mfma_fp4_peak(const void* operands, int iters, int workgroups, void* sink, void* stream) {
+  if (!operands || !sink) return SERQ_ENULL;
+  if (iters < 0 || workgroups <= 0 || workgroups > (1 << 20)) return SERQ_ESHAPE;
+  if (!aligned16(operands) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return SERQ_EALIGN;
+  return launch_mfma_fp4_peak(operands, iters, workgroups, 127, 127, sink, (hipStream_t)stream);
+}
+
 int serq_bench_read(const void* src, size_t bytes, int workgroups, void* sink, void* stream) {
   if (!src || !sink) return SERQ_ENULL;
   if ((bytes % 16) != 0 || workgroups <= 0 || workgroups > (1 << 20)) return SERQ_ESHAPE;

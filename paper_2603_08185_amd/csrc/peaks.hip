@@ -1,5 +1,5 @@
 // Two measuring sticks for the benchmark (not part of the layer): what this part sustains when it
-// does nothing but int8 MFMAs on operand bytes of the kind the layer feeds it, and what it sustains
+// does nothing but int8 (or block-scaled FP4) MFMAs on operand bytes of the kind the layer feeds it, and what it sustains
 // when it does nothing but read.  The datasheet peaks (5.0 POP/s, 8 TB/s) are never reached by any
 // kernel here -- the part is power-limited under MFMA load and a read of tens of megabytes is over
 // before the memory system is in full swing -- so the benchmark reports fractions of both.
@@ -39,6 +39,39 @@ __global__ __launch_bounds__(256) void mfma_peak_kernel(const v4i* __restrict__ 
   if (s == 0x7fffffff) sink[0] = s;                     // keeps the loop alive; practically never taken
 }
 
+// The same with the block-scaled FP4 MFMA (32x32x64): each 16-byte operand slot holds the 32 E2M1 codes
+// of a lane; byte 0 of scale_a / scale_b is the block exponent every lane uses (its value does not change the rate
+// of the instruction).
+__global__ __launch_bounds__(256) void mfma_fp4_peak_kernel(const v4i* __restrict__ operands, int iters, int scale_a,
+                                                            int scale_b, int* __restrict__ sink) {
+  v16f acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.0f;
+  v8i a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const v4i x = operands[threadIdx.x * 8 + i], y = operands[threadIdx.x * 8 + 4 + i];
+    a[i] = __builtin_shufflevector(x, x, 0, 1, 2, 3, -1, -1, -1, -1);
+    b[i] = __builtin_shufflevector(y, y, 0, 1, 2, 3, -1, -1, -1, -1);
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i * 4 + j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i * 4 + j], 4, 4, 0, scale_a,
+                                                                         0, scale_b);
+  }
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s += acc[i][e];
+  if (s == 1.2345678e-30f) sink[0] = 1;                 // keeps the loop alive; practically never taken
+}
+
 // Every 16-byte piece of [src, src + bytes) is read once; nothing else happens.
 __global__ __launch_bounds__(256) void read_peak_kernel(const u4* __restrict__ src, size_t n16, size_t per_wg,
                                                         int* __restrict__ sink) {
@@ -64,6 +97,13 @@ __global__ __launch_bounds__(256) void read_peak_kernel(const u4* __restrict__ s
 int launch_mfma_peak(const void* operands, int iters, int workgroups, void* sink, hipStream_t st) {
   hipLaunchKernelGGL(mfma_peak_kernel, dim3((unsigned)workgroups), dim3(256), 0, st, (const v4i*)operands, iters,
                      (int*)sink);
+  return hipGetLastError() == hipSuccess ? SERQ_OK : SERQ_EHIP;
+}
+
+int launch_mfma_fp4_peak(const void* operands, int iters, int workgroups, int scale_a, int scale_b, void* sink,
+                         hipStream_t st) {
+  hipLaunchKernelGGL(mfma_fp4_peak_kernel, dim3((unsigned)workgroups), dim3(256), 0, st, (const v4i*)operands, iters,
+                     scale_a, scale_b, (int*)sink);
   return hipGetLastError() == hipSuccess ? SERQ_OK : SERQ_EHIP;
 }
 

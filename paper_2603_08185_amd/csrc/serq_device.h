@@ -170,6 +170,8 @@ int launch_quantize_act(const void* X, int x_dtype, const float* s_inv, int64_t 
                         int abits, void* Xq, float* scale, hipStream_t st);
 
 int launch_mfma_peak(const void* operands, int iters, int workgroups, void* sink, hipStream_t st);
+int launch_mfma_fp4_peak(const void* operands, int iters, int workgroups, int scale_a, int scale_b, void* sink,
+                         hipStream_t st);
 int launch_read_peak(const void* src, size_t bytes, int workgroups, void* sink, hipStream_t st);
 
 // MXFP4 path (mx.hip, gemm_mx.hip)
