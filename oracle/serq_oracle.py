@@ -24,7 +24,9 @@ main + compensation == Q(X) . [W_s ; deq(Q(W_r))]; for the 4-bit compensation
 matrix a hand-worked example, the integer-matrix reduction, the scale/2 bound
 and the reduction to `linear` with the dequantised matrix; for MXFP4 the value
 table and tie cases of the format, hand-worked blocks, the power-of-two
-invariance, the error bound of the grid and brute force.  No function is unpinned.
+invariance, the error bound of the grid and brute force; for the gated product a
+library routine, the odd-part identity, limits and the reductions to the plain
+quantisers.  No function is unpinned.
 """
 from __future__ import annotations
 
@@ -298,6 +300,35 @@ def mx_linear(Xc, Xe, Wc, We, Rc=None, Re=None, s_begin: int = 0) -> np.ndarray:
         r = Rc.shape[1]
         Y = Y + Xd[:, s_begin:s_begin + r] @ mx_dequantize(Rc, Re).T
     return Y
+
+
+# ---------------------------------------------------------------------------
+# Producer side of the down projection: the gated product, quantised where it is made
+# (Sec. 3.2, "Offline Weight Permutation" / the decoder-layer flow of Fig. 2(b): the
+# input of the down projection is act(gate) * up in the permuted channel order, and the
+# flattening is merged into the adjacent step)
+# ---------------------------------------------------------------------------
+def silu(x: np.ndarray) -> np.ndarray:
+    """x * sigmoid(x) in fp64."""
+    x = np.asarray(x, dtype=np.float64)
+    with np.errstate(over="ignore"):
+        return x / (1.0 + np.exp(-x))
+
+
+def swiglu(gate: np.ndarray, up: np.ndarray) -> np.ndarray:
+    """silu(gate) * up, evaluated in fp64 and rounded once to fp32: the activations the
+    down projection would receive if the product were stored unrounded."""
+    return (silu(gate) * np.asarray(up, dtype=np.float64)).astype(F32)
+
+
+def swiglu_quantize_act(gate, up, s_inv, abits: int):
+    """quantize_act (Eq. 4 + Eq. 1) of the gated product."""
+    return quantize_act(swiglu(gate, up), s_inv, abits)
+
+
+def mx_swiglu_quantize_act(gate, up, s_inv):
+    """mx_quantize_act of the gated product."""
+    return mx_quantize_act(swiglu(gate, up), s_inv)
 
 
 def linear_f32(Xq, scale, Wq, wscale, R=None, s_begin: int = 0, acc=None) -> np.ndarray:

@@ -60,7 +60,10 @@ __device__ __forceinline__ uint32_t pack8(const uint32_t c[8]) {
 }
 
 // ---- activations ----------------------------------------------------------------------------------
-// One workgroup per token; a thread owns 8 consecutive channels, four neighbouring threads a block.
+// A thread owns 8 consecutive channels of one token (one 16-byte load of 16-bit input), four
+// neighbouring threads a block; grid = (tokens, pieces of 256 threads along the row).  Nothing is
+// shared between blocks, so every thread's loads are independent and the launch is one wave of
+// short workgroups.
 template <int XDT>
 __global__ __launch_bounds__(kT) void mx_quantize_act_kernel(const void* __restrict__ X, const float* __restrict__ s_inv,
                                                              int K, int64_t ldx, int64_t M, uint32_t* __restrict__ Xq,
@@ -70,65 +73,67 @@ __global__ __launch_bounds__(kT) void mx_quantize_act_kernel(const void* __restr
   const char* row = (const char*)X + (size_t)m * (size_t)ldx * esz;
   const int nchunk = K >> 3;
   const size_t Mp = (size_t)((M + 1) & ~(int64_t)1);
-  const int nround = (nchunk + kT - 1) / kT;                          // kT is a multiple of 4: blocks never straddle rounds
-  for (int rd = 0; rd < nround; ++rd) {
-    const int chunk = rd * kT + threadIdx.x;
-    const bool live = chunk < nchunk;
-    float v[8];
+  const int chunk = blockIdx.y * kT + threadIdx.x;
+  const bool live = chunk < nchunk;                                   // nchunk is a multiple of 4: a block is live or not as a whole
+  float v[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = 0.0f;
-    if (live) {
-      if constexpr (XDT == SERQ_F32) {
-        const float4* p = (const float4*)row + 2 * (size_t)chunk;
-        const float4 a = p[0], b = p[1];
-        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-      } else {
-        const uint4 u = ((const uint4*)row)[chunk];
-        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+  for (int i = 0; i < 8; ++i) v[i] = 0.0f;
+  if (live) {
+    if constexpr (XDT == SERQ_F32) {
+      const float4* p = (const float4*)row + 2 * (size_t)chunk;
+      const float4 a = p[0], b = p[1];
+      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    } else {
+      const uint4 u = ((const uint4*)row)[chunk];
+      const uint32_t w[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          if constexpr (XDT == SERQ_BF16) {
-            v[2 * i] = __uint_as_float(w[i] << 16);
-            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-          } else {
-            v[2 * i] = f16_to_f32((uint16_t)(w[i] & 0xffffu));
-            v[2 * i + 1] = f16_to_f32((uint16_t)(w[i] >> 16));
-          }
+      for (int i = 0; i < 4; ++i) {
+        if constexpr (XDT == SERQ_BF16) {
+          v[2 * i] = __uint_as_float(w[i] << 16);
+          v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        } else {
+          v[2 * i] = f16_to_f32((uint16_t)(w[i] & 0xffffu));
+          v[2 * i + 1] = f16_to_f32((uint16_t)(w[i] >> 16));
         }
       }
-      if (s_inv) {
-        const float4* p = (const float4*)s_inv + 2 * (size_t)chunk;
-        const float4 a = p[0], b = p[1];
-        v[0] *= a.x; v[1] *= a.y; v[2] *= a.z; v[3] *= a.w; v[4] *= b.x; v[5] *= b.y; v[6] *= b.z; v[7] *= b.w;
-      }
     }
-    float amax = 0.0f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(v[i]));
-    amax = fmaxf(amax, __shfl_xor(amax, 1, 64));
-    amax = fmaxf(amax, __shfl_xor(amax, 2, 64));
-    const int E = mx_exponent(amax);
-    if (live) {
-      uint32_t c[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) c[i] = e2m1_code(mx_scale_down(v[i], E));
-      Xq[(size_t)m * nchunk + chunk] = pack8(c);
-      if ((chunk & 3) == 0) {
-        const int blk = chunk >> 2;
-        xsc[((size_t)(blk >> 3) * Mp + (size_t)m) * 8 + (blk & 7)] = (uint8_t)E;
-      }
+    if (s_inv) {
+      const float4* p = (const float4*)s_inv + 2 * (size_t)chunk;
+      const float4 a = p[0], b = p[1];
+      v[0] *= a.x; v[1] *= a.y; v[2] *= a.z; v[3] *= a.w; v[4] *= b.x; v[5] *= b.y; v[6] *= b.z; v[7] *= b.w;
     }
   }
-  // scale bytes of the blocks that the last 256-channel tile does not have
+  float amax = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(v[i]));
+  amax = fmaxf(amax, __shfl_xor(amax, 1, 64));
+  amax = fmaxf(amax, __shfl_xor(amax, 2, 64));
+  const int E = mx_exponent(amax);
+  // the 8 exponent bytes of a 256-channel tile are contiguous: gather them from the 32 threads that
+  // hold them (every fourth lane speaks for its block) and store them as one 8-byte piece
+  const int lane = threadIdx.x & 63;
+  uint32_t lo = 0, hi = 0;
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    lo |= (uint32_t)__shfl(E, (lane & 32) + 4 * b, 64) << (8 * b);
+    hi |= (uint32_t)__shfl(E, (lane & 32) + 16 + 4 * b, 64) << (8 * b);
+  }
   const int nblk = K >> 5;
-  const int nblk8 = (nblk + 7) & ~7;
-  if ((int)threadIdx.x < nblk8 - nblk) {
-    const int blk = nblk + threadIdx.x;
-    xsc[((size_t)(blk >> 3) * Mp + (size_t)m) * 8 + (blk & 7)] = 127;
+  if (live) {
+    uint32_t c[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) c[i] = e2m1_code(mx_scale_down(v[i], E));
+    Xq[(size_t)m * nchunk + chunk] = pack8(c);
   }
-  // the padding row of an odd M
-  if (m == M - 1 && (size_t)M < Mp)
-    for (int blk = threadIdx.x; blk < nblk8; blk += kT) xsc[((size_t)(blk >> 3) * Mp + (size_t)M) * 8 + (blk & 7)] = 127;
+  if ((lane & 31) == 0) {
+    const int tile = chunk >> 5;                                      // 32 chunks = 256 channels
+    if (8 * tile < nblk) {
+      // blocks of the tile that the row does not have store 127 (their threads computed E = 127 from zeros)
+      *(uint2*)(xsc + ((size_t)tile * Mp + (size_t)m) * 8) = make_uint2(lo, hi);
+      if (m == M - 1 && (size_t)M < Mp)                               // the padding row of an odd M
+        *(uint2*)(xsc + ((size_t)tile * Mp + (size_t)M) * 8) = make_uint2(0x7f7f7f7fu, 0x7f7f7f7fu);
+    }
+  }
 }
 
 // ---- weights and compensation matrix ------------------------------------------------------------------
@@ -269,7 +274,7 @@ __global__ __launch_bounds__(kT) void mx_unpack_act_kernel(const uint32_t* __res
 
 int launch_mx_quantize_act(const void* X, int x_dtype, const float* s_inv, int64_t M, int K, int64_t ldx, void* Xq,
                            uint8_t* xsc, hipStream_t st) {
-  dim3 grid((unsigned)M), block(kT);
+  dim3 grid((unsigned)M, (unsigned)((K / 8 + kT - 1) / kT)), block(kT);
   if (x_dtype == SERQ_F32)
     hipLaunchKernelGGL(mx_quantize_act_kernel<SERQ_F32>, grid, block, 0, st, X, s_inv, K, ldx, M, (uint32_t*)Xq, xsc);
   else if (x_dtype == SERQ_F16)

@@ -404,3 +404,52 @@ def test_mx_pack_residual_and_compensation():
     assert np.linalg.norm(y1 - ref) < np.linalg.norm(y0 - ref)
     full = orc.mx_linear(Xc, Xe, pk["Wc"], pk["We"], pk["Rc"], pk["Re"])
     assert np.allclose(full, Xd @ Wd.T + Xd[:, :spec.r] @ Rd.T, rtol=1e-12, atol=1e-12)
+
+
+# ---------------------------------------------------------------------------
+# gated product (producer side of the down projection)
+# ---------------------------------------------------------------------------
+def test_silu_against_library_identity_and_limits():
+    import torch
+    x = np.concatenate([np.linspace(-30, 30, 2001), [0.0, 1.0, -1.0, 1e-8, -1e-8, 700.0, -700.0, 1e4, -1e4]])
+    y = orc.silu(x)
+    ref = torch.nn.functional.silu(torch.from_numpy(x)).numpy()          # library routine, fp64
+    assert np.allclose(y, ref, rtol=1e-14, atol=1e-300)
+    assert y[x == 0.0][0] == 0.0
+    assert abs(orc.silu(np.array([1.0]))[0] - 0.7310585786300049) < 1e-16   # 1 / (1 + e^-1)
+    # odd part: silu(x) - silu(-x) = x (sigmoid(x) + sigmoid(-x) = 1)
+    assert np.allclose(y - orc.silu(-x), x, rtol=1e-14, atol=1e-14)
+    assert orc.silu(np.array([700.0]))[0] == 700.0 and orc.silu(np.array([-1e4]))[0] == 0.0
+    assert np.all(np.isfinite(y))
+    # minimum of silu is about -0.2785 at x about -1.2785
+    assert abs(y.min() + 0.27846) < 1e-4
+
+
+def test_swiglu_reductions_to_the_plain_quantisers():
+    rng = np.random.default_rng(5)
+    M, K = 6, 128
+    g = rng.standard_normal((M, K)).astype(np.float32) * 3
+    u = rng.standard_normal((M, K)).astype(np.float32)
+    s_inv = rng.uniform(0.5, 2.0, K).astype(np.float32)
+    # up = 1: the product is silu itself
+    assert np.array_equal(orc.swiglu(g, np.ones_like(g)), orc.silu(g).astype(np.float32))
+    # a gate far in the linear region: silu(g) = g to the last bit, so the product is g * u rounded once
+    big = (np.abs(g) + 50).astype(np.float32)
+    assert np.array_equal(orc.swiglu(big, u), (big.astype(np.float64) * u).astype(np.float32))
+    for abits in (4, 8):
+        a = orc.swiglu_quantize_act(big, u, s_inv, abits)
+        b = orc.quantize_act((big.astype(np.float64) * u).astype(np.float32), s_inv, abits)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    a = orc.mx_swiglu_quantize_act(big, u, s_inv)
+    b = orc.mx_quantize_act((big.astype(np.float64) * u).astype(np.float32), s_inv)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    # a gate far in the negative region closes the gate: all-zero tokens, scale 1 / exponent byte 127
+    shut = np.full_like(g, -800.0)
+    codes, scale = orc.swiglu_quantize_act(shut, u, None, 8)
+    assert not codes.any() and np.all(scale == 1.0)
+    codes, E = orc.mx_swiglu_quantize_act(shut, u, None)
+    assert not codes.any() and np.all(E == 127)
+    # sign: a negative `up` flips every code (both grids are symmetric)
+    c1, s1 = orc.swiglu_quantize_act(g, u, s_inv, 8)
+    c2, s2 = orc.swiglu_quantize_act(g, -u, s_inv, 8)
+    assert np.array_equal(c1, -c2) and np.array_equal(s1, s2)
