@@ -149,6 +149,20 @@ int serq_quantize_act(const void* X, int x_dtype, const float* s_inv,
                       void* Xq_out, float* scale_out, void* stream);
 
 /*
+ * The same step fused into the producer of the down projection's input (Sec. 3.2, "Offline Weight
+ * Permutation" and the decoder-layer flow of Fig. 2(b): the gated product arrives in the permuted channel
+ * order and the flattening is merged into the adjacent step): the row that is flattened and quantised is
+ *   v[m,k] = silu(G[m,k]) * U[m,k],   silu(g) = g / (1 + exp(-g)),
+ * formed in fp32 and never rounded to a 16-bit type.  G, U [M,K] in x_dtype with row strides ldg, ldu
+ * (multiples of 8; the two may be halves of one [M,2K] buffer).  Everything else as serq_quantize_act.
+ * The exponential makes the product good to a few ulps of fp32, not bit-defined: a code may differ from
+ * the correctly rounded one where v / scale lies within that distance of a rounding boundary.
+ */
+int serq_swiglu_quantize_act(const void* G, const void* U, int x_dtype, const float* s_inv,
+                             int64_t M, int64_t K, int64_t ldg, int64_t ldu, int abits,
+                             void* Xq_out, float* scale_out, void* stream);
+
+/*
  * Online step 2: the SERQ linear layer (Eq. 2 + Eq. 7, first line)
  *
  *   Y[m,n] = scale[m] * ( wscale[n] * sum_k Xq[m,k]*Wq[n,k]
@@ -212,6 +226,10 @@ size_t serq_mx_weight_scale_bytes(int64_t N, int64_t K);
  * each token in blocks of 32 channels.  X [M,K] fp16/bf16/fp32, row stride ldx (multiple of 8). */
 int serq_mx_quantize_act(const void* X, int x_dtype, const float* s_inv, int64_t M, int64_t K, int64_t ldx,
                          void* Xq_out, uint8_t* xscale_out, void* stream);
+/* serq_mx_quantize_act of the gated product silu(G) * U (see serq_swiglu_quantize_act). */
+int serq_mx_swiglu_quantize_act(const void* G, const void* U, int x_dtype, const float* s_inv,
+                                int64_t M, int64_t K, int64_t ldg, int64_t ldu,
+                                void* Xq_out, uint8_t* xscale_out, void* stream);
 
 /* Offline preparation for the MXFP4 layer (Sec. 3.2 with Q = MXFP4): W~ = (W * s)[:, perm] in fp32
  * (s, perm_in, perm_out, s_inv_out as in serq_pack_weights), MXFP4 per output channel in blocks of 32

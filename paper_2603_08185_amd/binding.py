@@ -41,6 +41,8 @@ SIGNATURES = {
     "serq_unpack_weights": (_i, [_vp, _i64, _i64, _vp, _vp]),
     "serq_unpack_act": (_i, [_vp, _i, _i64, _i64, _vp, _vp]),
     "serq_quantize_act": (_i, [_vp, _i, _vp, _i64, _i64, _i64, _i, _vp, _vp, _vp]),
+    "serq_swiglu_quantize_act": (_i, [_vp, _vp, _i, _vp, _i64, _i64, _i64, _i64, _i, _vp, _vp, _vp]),
+    "serq_mx_swiglu_quantize_act": (_i, [_vp, _vp, _i, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
     "serq_linear": (_i, [_vp, _vp, _i, _vp, _vp, _i, _i, _vp, _i, _i64, _i64, _i64, _vp, _i, _i64,
                          _vp, _sz, _i, _vp]),
     "serq_gemm_i32": (_i, [_vp, _i, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _sz, _i, _vp]),
@@ -217,6 +219,51 @@ def quantize_act(X: torch.Tensor, s_inv: Optional[torch.Tensor], abits: int,
     rc = L.serq_quantize_act(_ptr(X), _DT[X.dtype], _ptr(s_inv), M, K, ldx, abits, _ptr(Xq), _ptr(scale), _stream())
     _check("serq_quantize_act", rc)
     return Xq, scale
+
+
+def _rows(T: torch.Tensor, what: str):
+    if not T.is_cuda:
+        raise ValueError(f"{what} must live in device memory")
+    if T.dim() != 2 or T.stride(1) != 1:
+        raise ValueError(f"{what} must be [M,K] with unit inner stride")
+
+
+def swiglu_quantize_act(G: torch.Tensor, U: torch.Tensor, s_inv: Optional[torch.Tensor], abits: int,
+                        Xq: Optional[torch.Tensor] = None, scale: Optional[torch.Tensor] = None):
+    """serq_swiglu_quantize_act: quantize_act of silu(G) * U; returns (Xq packed uint8 blob, scale fp32 [M])."""
+    _rows(G, "G")
+    _rows(U, "U")
+    if G.shape != U.shape or G.dtype != U.dtype:
+        raise ValueError("G and U must agree in shape and dtype")
+    M, K = G.shape
+    L = lib()
+    if Xq is None:
+        Xq = torch.empty(max(L.serq_packed_act_bytes(M, K, abits), 16), dtype=torch.uint8, device=G.device)
+    if scale is None:
+        scale = torch.empty(max(M, 1), dtype=torch.float32, device=G.device)[:M]
+    rc = L.serq_swiglu_quantize_act(_ptr(G), _ptr(U), _DT[G.dtype], _ptr(s_inv), M, K, G.stride(0) if M > 0 else K,
+                                    U.stride(0) if M > 0 else K, abits, _ptr(Xq), _ptr(scale), _stream())
+    _check("serq_swiglu_quantize_act", rc)
+    return Xq, scale
+
+
+def mx_swiglu_quantize_act(G: torch.Tensor, U: torch.Tensor, s_inv: Optional[torch.Tensor],
+                           Xq: Optional[torch.Tensor] = None, xsc: Optional[torch.Tensor] = None):
+    """serq_mx_swiglu_quantize_act: mx_quantize_act of silu(G) * U; returns (codes blob, block-scale blob)."""
+    _rows(G, "G")
+    _rows(U, "U")
+    if G.shape != U.shape or G.dtype != U.dtype:
+        raise ValueError("G and U must agree in shape and dtype")
+    M, K = G.shape
+    L = lib()
+    if Xq is None:
+        Xq = torch.empty(max(L.serq_packed_act_bytes(M, K, 4), 16), dtype=torch.uint8, device=G.device)
+    if xsc is None:
+        xsc = torch.empty(max(L.serq_mx_act_scale_bytes(M, K), 16), dtype=torch.uint8, device=G.device)
+    rc = L.serq_mx_swiglu_quantize_act(_ptr(G), _ptr(U), _DT[G.dtype], _ptr(s_inv), M, K, G.stride(0) if M > 0 else K,
+                                       U.stride(0) if M > 0 else K, _ptr(Xq), _ptr(xsc), _stream())
+    _check("serq_mx_swiglu_quantize_act", rc)
+    return Xq, xsc
 
 
 def linear(Xq: torch.Tensor, scale: torch.Tensor, abits: int, Wq: torch.Tensor, wscale: torch.Tensor,

@@ -165,7 +165,24 @@ int serq_quantize_act(const void* X, int x_dtype, const float* s_inv,
   if (!X || !Xq_out || !scale_out) return SERQ_ENULL;
   if (!aligned16(X) || !aligned16(Xq_out) || !aligned16(s_inv) || (reinterpret_cast<uintptr_t>(scale_out) & 3u))
     return SERQ_EALIGN;
-  return launch_quantize_act(X, x_dtype, s_inv, M, (int)K, ldx, abits, Xq_out, scale_out, (hipStream_t)stream);
+  return launch_quantize_act(X, nullptr, x_dtype, s_inv, M, (int)K, ldx, 0, abits, Xq_out, scale_out,
+                             (hipStream_t)stream);
+}
+
+int serq_swiglu_quantize_act(const void* G, const void* U, int x_dtype, const float* s_inv,
+                             int64_t M, int64_t K, int64_t ldg, int64_t ldu, int abits,
+                             void* Xq_out, float* scale_out, void* stream) {
+  if (abits != 4 && abits != 8) return SERQ_EDTYPE;
+  if (!dtype_ok(x_dtype)) return SERQ_EDTYPE;
+  if (M < 0 || K < 64 || K > 131072 || (K % 64) != 0) return SERQ_ESHAPE;
+  if (ldg < K || ldu < K) return SERQ_ESHAPE;
+  if ((ldg % 8) != 0 || (ldu % 8) != 0) return SERQ_EALIGN;
+  if (M == 0) return SERQ_OK;
+  if (!G || !U || !Xq_out || !scale_out) return SERQ_ENULL;
+  if (!aligned16(G) || !aligned16(U) || !aligned16(Xq_out) || !aligned16(s_inv) ||
+      (reinterpret_cast<uintptr_t>(scale_out) & 3u))
+    return SERQ_EALIGN;
+  return launch_quantize_act(G, U, x_dtype, s_inv, M, (int)K, ldg, ldu, abits, Xq_out, scale_out, (hipStream_t)stream);
 }
 
 static int linear_common(LinearArgs& a, int64_t M, int64_t N, int64_t K, int flags, void* stream) {
@@ -251,7 +268,21 @@ int serq_mx_quantize_act(const void* X, int x_dtype, const float* s_inv, int64_t
   if (M == 0) return SERQ_OK;
   if (!X || !Xq_out || !xscale_out) return SERQ_ENULL;
   if (!aligned16(X) || !aligned16(Xq_out) || !aligned16(s_inv) || !aligned16(xscale_out)) return SERQ_EALIGN;
-  return launch_mx_quantize_act(X, x_dtype, s_inv, M, (int)K, ldx, Xq_out, xscale_out, (hipStream_t)stream);
+  return launch_mx_quantize_act(X, nullptr, x_dtype, s_inv, M, (int)K, ldx, 0, Xq_out, xscale_out, (hipStream_t)stream);
+}
+
+int serq_mx_swiglu_quantize_act(const void* G, const void* U, int x_dtype, const float* s_inv,
+                                int64_t M, int64_t K, int64_t ldg, int64_t ldu,
+                                void* Xq_out, uint8_t* xscale_out, void* stream) {
+  if (!dtype_ok(x_dtype)) return SERQ_EDTYPE;
+  if (M < 0 || M > 0x7fffffff || K < 64 || K > 131072 || (K % 64) != 0) return SERQ_ESHAPE;
+  if (ldg < K || ldu < K) return SERQ_ESHAPE;
+  if ((ldg % 8) != 0 || (ldu % 8) != 0) return SERQ_EALIGN;
+  if (M == 0) return SERQ_OK;
+  if (!G || !U || !Xq_out || !xscale_out) return SERQ_ENULL;
+  if (!aligned16(G) || !aligned16(U) || !aligned16(Xq_out) || !aligned16(s_inv) || !aligned16(xscale_out))
+    return SERQ_EALIGN;
+  return launch_mx_quantize_act(G, U, x_dtype, s_inv, M, (int)K, ldg, ldu, Xq_out, xscale_out, (hipStream_t)stream);
 }
 
 int serq_mx_pack_weights(const void* W, int w_dtype, const float* s, const int32_t* perm_in,

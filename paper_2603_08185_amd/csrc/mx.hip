@@ -64,9 +64,35 @@ __device__ __forceinline__ uint32_t pack8(const uint32_t c[8]) {
 // neighbouring threads a block; grid = (tokens, pieces of 256 threads along the row).  Nothing is
 // shared between blocks, so every thread's loads are independent and the launch is one wave of
 // short workgroups.
+// 8 consecutive channels of a row, as fp32
 template <int XDT>
-__global__ __launch_bounds__(kT) void mx_quantize_act_kernel(const void* __restrict__ X, const float* __restrict__ s_inv,
-                                                             int K, int64_t ldx, int64_t M, uint32_t* __restrict__ Xq,
+__device__ __forceinline__ void load8(const char* row, int chunk, float v[8]) {
+  if constexpr (XDT == SERQ_F32) {
+    const float4* p = (const float4*)row + 2 * (size_t)chunk;
+    const float4 a = p[0], b = p[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  } else {
+    const uint4 u = ((const uint4*)row)[chunk];
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if constexpr (XDT == SERQ_BF16) {
+        v[2 * i] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+      } else {
+        v[2 * i] = f16_to_f32((uint16_t)(w[i] & 0xffffu));
+        v[2 * i + 1] = f16_to_f32((uint16_t)(w[i] >> 16));
+      }
+    }
+  }
+}
+
+// GLU: the row is the gated product silu(X) * U formed in fp32 (the input of the down projection,
+// quantised where it is made; Sec. 3.2, the decoder-layer flow of Fig. 2(b)).
+template <int XDT, bool GLU>
+__global__ __launch_bounds__(kT) void mx_quantize_act_kernel(const void* __restrict__ X, const void* __restrict__ U,
+                                                             const float* __restrict__ s_inv, int K, int64_t ldx,
+                                                             int64_t ldu, int64_t M, uint32_t* __restrict__ Xq,
                                                              uint8_t* __restrict__ xsc) {
   const int64_t m = blockIdx.x;
   constexpr size_t esz = (XDT == SERQ_F32) ? 4 : 2;
@@ -79,23 +105,12 @@ __global__ __launch_bounds__(kT) void mx_quantize_act_kernel(const void* __restr
 #pragma unroll
   for (int i = 0; i < 8; ++i) v[i] = 0.0f;
   if (live) {
-    if constexpr (XDT == SERQ_F32) {
-      const float4* p = (const float4*)row + 2 * (size_t)chunk;
-      const float4 a = p[0], b = p[1];
-      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-    } else {
-      const uint4 u = ((const uint4*)row)[chunk];
-      const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+    load8<XDT>(row, chunk, v);
+    if constexpr (GLU) {
+      float u[8];
+      load8<XDT>((const char*)U + (size_t)m * (size_t)ldu * esz, chunk, u);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        if constexpr (XDT == SERQ_BF16) {
-          v[2 * i] = __uint_as_float(w[i] << 16);
-          v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-        } else {
-          v[2 * i] = f16_to_f32((uint16_t)(w[i] & 0xffffu));
-          v[2 * i + 1] = f16_to_f32((uint16_t)(w[i] >> 16));
-        }
-      }
+      for (int i = 0; i < 8; ++i) v[i] = silu_mul(v[i], u[i]);
     }
     if (s_inv) {
       const float4* p = (const float4*)s_inv + 2 * (size_t)chunk;
@@ -272,15 +287,20 @@ __global__ __launch_bounds__(kT) void mx_unpack_act_kernel(const uint32_t* __res
 
 }  // namespace
 
-int launch_mx_quantize_act(const void* X, int x_dtype, const float* s_inv, int64_t M, int K, int64_t ldx, void* Xq,
-                           uint8_t* xsc, hipStream_t st) {
+int launch_mx_quantize_act(const void* X, const void* U, int x_dtype, const float* s_inv, int64_t M, int K, int64_t ldx,
+                           int64_t ldu, void* Xq, uint8_t* xsc, hipStream_t st) {
   dim3 grid((unsigned)M, (unsigned)((K / 8 + kT - 1) / kT)), block(kT);
-  if (x_dtype == SERQ_F32)
-    hipLaunchKernelGGL(mx_quantize_act_kernel<SERQ_F32>, grid, block, 0, st, X, s_inv, K, ldx, M, (uint32_t*)Xq, xsc);
-  else if (x_dtype == SERQ_F16)
-    hipLaunchKernelGGL(mx_quantize_act_kernel<SERQ_F16>, grid, block, 0, st, X, s_inv, K, ldx, M, (uint32_t*)Xq, xsc);
-  else
-    hipLaunchKernelGGL(mx_quantize_act_kernel<SERQ_BF16>, grid, block, 0, st, X, s_inv, K, ldx, M, (uint32_t*)Xq, xsc);
+#define SERQ_MXQ_LAUNCH(XDT)                                                                                          \
+  do {                                                                                                                \
+    if (U) hipLaunchKernelGGL((mx_quantize_act_kernel<XDT, true>), grid, block, 0, st, X, U, s_inv, K, ldx, ldu, M,   \
+                              (uint32_t*)Xq, xsc);                                                                    \
+    else hipLaunchKernelGGL((mx_quantize_act_kernel<XDT, false>), grid, block, 0, st, X, U, s_inv, K, ldx, ldu, M,    \
+                            (uint32_t*)Xq, xsc);                                                                      \
+  } while (0)
+  if (x_dtype == SERQ_F32) SERQ_MXQ_LAUNCH(SERQ_F32);
+  else if (x_dtype == SERQ_F16) SERQ_MXQ_LAUNCH(SERQ_F16);
+  else SERQ_MXQ_LAUNCH(SERQ_BF16);
+#undef SERQ_MXQ_LAUNCH
   return ok();
 }
 

@@ -12,6 +12,11 @@
 // round-to-nearest-even (codes8 below avoids most of the divisions without
 // changing any result), so the codes do not depend on how the reduction is
 // scheduled.
+//
+// GLU variants: the token row is the gated product silu(gate) * up of two inputs (the input of the
+// down projection, quantised where it is made instead of being stored in 16 bits and read back;
+// Sec. 3.2, the decoder-layer flow of Fig. 2(b)).  The product is formed in fp32 (expf to an ulp, IEEE
+// division) and never rounded to the storage type.
 #include "serq_device.h"
 
 namespace serq {
@@ -40,6 +45,15 @@ __device__ __forceinline__ void load8(const void* row, int chunk, float v[8]) {
       }
     }
   }
+}
+
+// v <- silu(v) * u, elementwise
+template <int XDT>
+__device__ __forceinline__ void glu8(const void* urow, int chunk, float v[8]) {
+  float u[8];
+  load8<XDT>(urow, chunk, u);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = serq::silu_mul(v[i], u[i]);
 }
 
 __device__ __forceinline__ void flatten8(const float* s_inv, int chunk, float v[8]) {
@@ -121,15 +135,16 @@ __device__ __forceinline__ float block_max(float m, float* red) {
 
 // NC = 16-byte pieces (8 channels each) a thread keeps in registers; NC = 0 is
 // the any-K variant that reads the row a second time (from L2).
-template <int XDT, int ABITS, int NC>
+template <int XDT, int ABITS, int NC, bool GLU>
 __global__ __launch_bounds__(kThreads) void quantize_act_kernel(
-    const void* __restrict__ X, const float* __restrict__ s_inv, int K, int64_t ldx,
-    void* __restrict__ Xq, float* __restrict__ scale) {
+    const void* __restrict__ X, const void* __restrict__ U, const float* __restrict__ s_inv, int K, int64_t ldx,
+    int64_t ldu, void* __restrict__ Xq, float* __restrict__ scale) {
   __shared__ float red[kThreads / 64];
   const int64_t m = blockIdx.x;
   const int nchunk = K >> 3;
   constexpr size_t esz = (XDT == SERQ_F32) ? 4 : 2;
   const char* row = (const char*)X + (size_t)m * (size_t)ldx * esz;
+  const char* urow = GLU ? (const char*)U + (size_t)m * (size_t)ldu * esz : nullptr;
   char* xq_row = (char*)Xq + (size_t)m * ((size_t)K * ABITS / 8);
   constexpr float q = (float)((1 << (ABITS - 1)) - 1);
 
@@ -141,6 +156,7 @@ __global__ __launch_bounds__(kThreads) void quantize_act_kernel(
       const int chunk = threadIdx.x + c * kThreads;
       if (chunk < nchunk) {
         load8<XDT>(row, chunk, v[c]);
+        if constexpr (GLU) glu8<XDT>(urow, chunk, v[c]);
         flatten8(s_inv, chunk, v[c]);
         amax = absmax8(v[c], amax);
       }
@@ -158,6 +174,7 @@ __global__ __launch_bounds__(kThreads) void quantize_act_kernel(
     for (int chunk = threadIdx.x; chunk < nchunk; chunk += kThreads) {
       float v[8];
       load8<XDT>(row, chunk, v);
+      if constexpr (GLU) glu8<XDT>(urow, chunk, v);
       flatten8(s_inv, chunk, v);
       amax = absmax8(v, amax);
     }
@@ -167,52 +184,57 @@ __global__ __launch_bounds__(kThreads) void quantize_act_kernel(
     for (int chunk = threadIdx.x; chunk < nchunk; chunk += kThreads) {
       float v[8];
       load8<XDT>(row, chunk, v);
+      if constexpr (GLU) glu8<XDT>(urow, chunk, v);
       flatten8(s_inv, chunk, v);
       quant_store8<ABITS>(v, sc, xq_row, chunk);
     }
   }
 }
 
-template <int XDT, int ABITS>
-int launch_t(const void* X, const float* s_inv, int64_t M, int K, int64_t ldx, void* Xq, float* scale,
-             hipStream_t st) {
+template <int XDT, int ABITS, bool GLU>
+int launch_t(const void* X, const void* U, const float* s_inv, int64_t M, int K, int64_t ldx, int64_t ldu, void* Xq,
+             float* scale, hipStream_t st) {
   const int nchunk = K >> 3;
   const int per = (nchunk + kThreads - 1) / kThreads;
   dim3 grid((unsigned)M), block(kThreads);
-  if (per <= 1)
-    hipLaunchKernelGGL((quantize_act_kernel<XDT, ABITS, 1>), grid, block, 0, st, X, s_inv, K, ldx, Xq, scale);
-  else if (per <= 2)
-    hipLaunchKernelGGL((quantize_act_kernel<XDT, ABITS, 2>), grid, block, 0, st, X, s_inv, K, ldx, Xq, scale);
-  else if (per <= 4)
-    hipLaunchKernelGGL((quantize_act_kernel<XDT, ABITS, 4>), grid, block, 0, st, X, s_inv, K, ldx, Xq, scale);
-  else if (per <= 8)
-    hipLaunchKernelGGL((quantize_act_kernel<XDT, ABITS, 8>), grid, block, 0, st, X, s_inv, K, ldx, Xq, scale);
-  else
-    hipLaunchKernelGGL((quantize_act_kernel<XDT, ABITS, 0>), grid, block, 0, st, X, s_inv, K, ldx, Xq, scale);
+#define SERQ_QA_LAUNCH(NC) \
+  hipLaunchKernelGGL((quantize_act_kernel<XDT, ABITS, NC, GLU>), grid, block, 0, st, X, U, s_inv, K, ldx, ldu, Xq, scale)
+  if (per <= 1) SERQ_QA_LAUNCH(1);
+  else if (per <= 2) SERQ_QA_LAUNCH(2);
+  else if (per <= 4) SERQ_QA_LAUNCH(4);
+  else if (per <= 8) SERQ_QA_LAUNCH(8);
+  else SERQ_QA_LAUNCH(0);
+#undef SERQ_QA_LAUNCH
   return hipGetLastError() == hipSuccess ? SERQ_OK : SERQ_EHIP;
 }
 
 template <int XDT>
-int launch_b(const void* X, const float* s_inv, int64_t M, int K, int64_t ldx, int abits, void* Xq,
-             float* scale, hipStream_t st) {
-  return abits == 4 ? launch_t<XDT, 4>(X, s_inv, M, K, ldx, Xq, scale, st)
-                    : launch_t<XDT, 8>(X, s_inv, M, K, ldx, Xq, scale, st);
+int launch_b(const void* X, const void* U, const float* s_inv, int64_t M, int K, int64_t ldx, int64_t ldu, int abits,
+             void* Xq, float* scale, hipStream_t st) {
+  if (U) {
+    return abits == 4 ? launch_t<XDT, 4, true>(X, U, s_inv, M, K, ldx, ldu, Xq, scale, st)
+                      : launch_t<XDT, 8, true>(X, U, s_inv, M, K, ldx, ldu, Xq, scale, st);
+  }
+  return abits == 4 ? launch_t<XDT, 4, false>(X, nullptr, s_inv, M, K, ldx, 0, Xq, scale, st)
+                    : launch_t<XDT, 8, false>(X, nullptr, s_inv, M, K, ldx, 0, Xq, scale, st);
 }
 
 }  // namespace
 
-int launch_quantize_act(const void* X, int x_dtype, const float* s_inv, int64_t M, int K, int64_t ldx,
-                        int abits, void* Xq, float* scale, hipStream_t st) {
+// U != nullptr: the row is silu(X) * U (same dtype, row stride ldu)
+int launch_quantize_act(const void* X, const void* U, int x_dtype, const float* s_inv, int64_t M, int K, int64_t ldx,
+                        int64_t ldu, int abits, void* Xq, float* scale, hipStream_t st) {
   // the grid's x dimension carries the token index
   for (int64_t m0 = 0; m0 < M; m0 += (1 << 30)) {
     const int64_t mc = (M - m0) < (1 << 30) ? (M - m0) : (1 << 30);
     const size_t esz = x_dtype == SERQ_F32 ? 4 : 2;
     const void* Xs = (const char*)X + (size_t)m0 * (size_t)ldx * esz;
+    const void* Us = U ? (const char*)U + (size_t)m0 * (size_t)ldu * esz : nullptr;
     void* Xqs = (char*)Xq + (size_t)m0 * ((size_t)K * abits / 8);
     int rc;
-    if (x_dtype == SERQ_F32) rc = launch_b<SERQ_F32>(Xs, s_inv, mc, K, ldx, abits, Xqs, scale + m0, st);
-    else if (x_dtype == SERQ_F16) rc = launch_b<SERQ_F16>(Xs, s_inv, mc, K, ldx, abits, Xqs, scale + m0, st);
-    else rc = launch_b<SERQ_BF16>(Xs, s_inv, mc, K, ldx, abits, Xqs, scale + m0, st);
+    if (x_dtype == SERQ_F32) rc = launch_b<SERQ_F32>(Xs, Us, s_inv, mc, K, ldx, ldu, abits, Xqs, scale + m0, st);
+    else if (x_dtype == SERQ_F16) rc = launch_b<SERQ_F16>(Xs, Us, s_inv, mc, K, ldx, ldu, abits, Xqs, scale + m0, st);
+    else rc = launch_b<SERQ_BF16>(Xs, Us, s_inv, mc, K, ldx, ldu, abits, Xqs, scale + m0, st);
     if (rc != SERQ_OK) return rc;
   }
   return SERQ_OK;

@@ -67,6 +67,8 @@ __device__ __forceinline__ v4i as_v4i(const u4& p) { return __builtin_bit_cast(v
 // storage-type helpers -------------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
 __device__ __forceinline__ float f16_to_f32(uint16_t u) { return (float)__builtin_bit_cast(_Float16, u); }
+// silu(g) * u in fp32: expf to an ulp, IEEE division; g -> -inf gives -0 * u, g -> +inf gives g * u
+__device__ __forceinline__ float silu_mul(float g, float u) { return (g / (1.0f + expf(-g))) * u; }
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   v2f x = {f, 0.0f};
@@ -166,8 +168,8 @@ struct LinearArgs {
 size_t skinny_workspace_bytes(int N);
 int launch_skinny(const LinearArgs& a, hipStream_t st);
 int launch_mfma(const LinearArgs& a, hipStream_t st);
-int launch_quantize_act(const void* X, int x_dtype, const float* s_inv, int64_t M, int K, int64_t ldx,
-                        int abits, void* Xq, float* scale, hipStream_t st);
+int launch_quantize_act(const void* X, const void* U, int x_dtype, const float* s_inv, int64_t M, int K, int64_t ldx,
+                        int64_t ldu, int abits, void* Xq, float* scale, hipStream_t st);
 
 int launch_mfma_peak(const void* operands, int iters, int workgroups, void* sink, hipStream_t st);
 int launch_mfma_fp4_peak(const void* operands, int iters, int workgroups, int scale_a, int scale_b, void* sink,
@@ -183,8 +185,8 @@ struct MxLinearArgs {
   void* Y; int y_dtype; int64_t ldy;
   int coltiles;
 };
-int launch_mx_quantize_act(const void* X, int x_dtype, const float* s_inv, int64_t M, int K, int64_t ldx, void* Xq,
-                           uint8_t* xsc, hipStream_t st);
+int launch_mx_quantize_act(const void* X, const void* U, int x_dtype, const float* s_inv, int64_t M, int K, int64_t ldx,
+                           int64_t ldu, void* Xq, uint8_t* xsc, hipStream_t st);
 int mx_pack_weights_impl(const void* W, int w_dtype, const float* s, const int32_t* perm, int N, int K, int r,
                          void* Wq, uint8_t* wsc, void* Rq, uint8_t* rsc, hipStream_t st);
 int mx_unpack_weights_impl(const void* Wq, const uint8_t* wsc, int N, int K, uint8_t* codes, uint8_t* E, hipStream_t st);
