@@ -382,6 +382,34 @@ def sweep():
         if r:
             lin_q4r(0)
             row["serq_linear_q4r_us"] = round(_time_launches(lin_q4r, n, graph=small), 2)
+        if "down" in spec.name:
+            # the down projection's input quantised where it is made: silu(gate) * up -> codes in one pass
+            gg = torch.Generator().manual_seed(1000 * spec.cfg + 11)
+            G = (torch.randn((M, K), generator=gg) * 2.5).to(torch.bfloat16).to(dev)
+            U = (torch.randn((M, K), generator=gg) * 1.5).to(torch.bfloat16).to(dev)
+
+            def sq(i):
+                serq.swiglu_quantize_act(G, U, pk.s_inv, spec.abits, Xq=Xq, scale=scale)
+
+            sq(0)
+            sq_us = _time_launches(sq, n, graph=small)
+            sq_bytes = 4.0 * M * K + M * K * spec.abits / 8 + 4 * M
+            row["swiglu_quantize_act"] = {"us": round(sq_us, 2), "gbs": round(sq_bytes / sq_us / 1e3, 1),
+                                          "frac_hbm_peak": round(sq_bytes / sq_us / 1e3 / HBM_PEAK_GBS, 4)}
+            if not small:
+                xsc_g = torch.empty(max(serq.lib().serq_mx_act_scale_bytes(M, K), 16), dtype=torch.uint8, device=dev)
+                Xq4_g = torch.empty(M * K // 2, dtype=torch.uint8, device=dev)
+
+                def msq(i):
+                    serq.mx_swiglu_quantize_act(G, U, pk.s_inv, Xq=Xq4_g, xsc=xsc_g)
+
+                msq(0)
+                msq_us = _time_launches(msq, n)
+                msq_bytes = 4.0 * M * K + M * K / 2 + M * K / 32
+                row["mx_swiglu_quantize_act"] = {"us": round(msq_us, 2), "gbs": round(msq_bytes / msq_us / 1e3, 1),
+                                                 "frac_hbm_peak": round(msq_bytes / msq_us / 1e3 / HBM_PEAK_GBS, 4)}
+                del xsc_g, Xq4_g
+            del G, U
         if small:
             b = decode_bytes(spec)
             row.update({"bound": "hbm", "gbs": round(b / l_us / 1e3, 1), "frac": round(b / l_us / 1e3 / HBM_PEAK_GBS, 4)})
