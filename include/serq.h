@@ -208,8 +208,9 @@ int serq_gemm_i32(const void* Xq, int abits, const void* Wq,
  * Weights, activations and the compensation matrix (along its rank index) all take this form (Eq. 7,
  * second line, with Q = MXFP4), so the layer is
  *   Y[m,n] = sum_k X^[m,k] W^[n,k] + sum_{j<r} X^[m,s_begin+j] R^[n,j]
- * with no further scales.  It runs on the block-scaled FP4 matrix instructions; there is no decode
- * (skinny) variant of it.
+ * with no further scales.  It runs on the block-scaled FP4 matrix instructions, in a tiled kernel for
+ * M > 32 and a weight-streaming kernel for M <= 32 (SERQ_PATH_* as for serq_linear; the streaming kernel
+ * does not slice K and takes no workspace).
  *
  * Buffers (device memory, 16-byte aligned; opaque except through the unpack calls):
  *   activation codes  serq_packed_act_bytes(M,K,4) bytes
@@ -251,7 +252,7 @@ int serq_mx_unpack_act(const void* Xq, const uint8_t* xscale, int64_t M, int64_t
 /* The MXFP4 layer.  Y [M,N] in y_dtype, row stride ldy (multiple of 8, >= N); fp32 accumulation over
  * k in the order of the hardware's 64-channel steps, the compensation sum added to the same
  * accumulators.  s_begin is a multiple of 256 with s_begin + 64*ceil(r/64) <= K; r a multiple of 32;
- * Rq may be NULL (no compensation).  flags: SERQ_FLAG_COLTILES only.  M = 0 is a no-op. */
+ * Rq may be NULL (no compensation).  flags: SERQ_PATH_* | SERQ_FLAG_COLTILES.  M = 0 is a no-op. */
 int serq_mx_linear(const void* Xq, const uint8_t* xscale, const void* Wq, const uint8_t* wscale,
                    int s_begin, int r, const void* Rq, const uint8_t* rscale,
                    int64_t M, int64_t N, int64_t K,

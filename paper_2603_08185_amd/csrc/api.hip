@@ -345,7 +345,11 @@ int serq_mx_linear(const void* Xq, const uint8_t* xscale, const void* Wq, const 
   a.M = (int)M; a.N = (int)N; a.K = (int)K;
   a.Y = Y; a.y_dtype = y_dtype; a.ldy = ldy;
   a.coltiles = (flags >> 20) & 0x7ff;
-  return launch_mx_linear(a, (hipStream_t)stream);
+  const int path = flags & 0xff;
+  if (path != SERQ_PATH_AUTO && path != SERQ_PATH_SKINNY && path != SERQ_PATH_MFMA) return SERQ_EUNSUPPORTED;
+  if (path == SERQ_PATH_SKINNY && M > 32) return SERQ_ESHAPE;
+  const bool skinny = path == SERQ_PATH_SKINNY || (path == SERQ_PATH_AUTO && M <= 32);
+  return skinny ? launch_skinny_mx(a, (hipStream_t)stream) : launch_mx_linear(a, (hipStream_t)stream);
 }
 
 int serq_bench_mfma_peak(const void* operands, int iters, int workgroups, void* sink, void* stream) {

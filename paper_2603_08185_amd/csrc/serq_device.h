@@ -192,6 +192,7 @@ int mx_pack_weights_impl(const void* W, int w_dtype, const float* s, const int32
 int mx_unpack_weights_impl(const void* Wq, const uint8_t* wsc, int N, int K, uint8_t* codes, uint8_t* E, hipStream_t st);
 int mx_unpack_act_impl(const void* Xq, const uint8_t* xsc, int64_t M, int K, uint8_t* codes, uint8_t* E, hipStream_t st);
 int launch_mx_linear(const MxLinearArgs& a, hipStream_t st);
+int launch_skinny_mx(const MxLinearArgs& a, hipStream_t st);
 
 int pack_weights_impl(const void* W, int w_dtype, const float* s, const int32_t* perm_in, int N, int K, int r,
                       void* Wq_out, float* wscale_out, int32_t* perm_out, float* s_inv_out, void* R_out,

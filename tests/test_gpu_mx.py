@@ -134,7 +134,7 @@ def test_mx_pack_zero_rows_and_blocks():
 # ---------------------------------------------------------------------------
 # the layer
 # ---------------------------------------------------------------------------
-def _run_mx(spec, rows=None, s_begin=0, with_R=True, coltiles=0):
+def _run_mx(spec, rows=None, s_begin=0, with_R=True, coltiles=0, path=serq.PATH_AUTO, cols=None):
     L = workloads.make_layer(spec, want=("X", "s", "W"))
     pk_o = orc.mx_pack_weights(f32(L["W"]), L["s"].numpy(), spec.r)
     pk = serq.mx_pack_weights(L["W"].to(DEV), L["s"].to(DEV), spec.r)
@@ -150,10 +150,13 @@ def _run_mx(spec, rows=None, s_begin=0, with_R=True, coltiles=0):
     use_R = with_R and spec.r > 0
     Y = serq.mx_linear(Xq, xsc, pk.Wq, pk.wsc, spec.M, spec.N, spec.K, Rq=pk.Rq if use_R else None,
                        rsc=pk.rsc if use_R else None, r=spec.r if use_R else 0, s_begin=s_begin,
-                       out_dtype=DT[spec.out_dtype], flags_=serq.flags(serq.PATH_AUTO, coltiles=coltiles))
-    Y64 = orc.mx_linear(Xc_o, Xe_o, pk_o["Wc"], pk_o["We"], pk_o["Rc"] if use_R else None,
-                        pk_o["Re"] if use_R else None, s_begin=s_begin)
+                       out_dtype=DT[spec.out_dtype], flags_=serq.flags(path, coltiles=coltiles))
+    csel = slice(None) if cols is None else np.asarray(cols)         # oracle on a sample of the output channels
+    Y64 = orc.mx_linear(Xc_o, Xe_o, pk_o["Wc"][csel], pk_o["We"][csel], pk_o["Rc"][csel] if use_R else None,
+                        pk_o["Re"][csel] if use_R else None, s_begin=s_begin)
     Ysel = Y if rows is None else Y[torch.as_tensor(np.asarray(rows), device=Y.device)]
+    if cols is not None:
+        Ysel = Ysel[:, torch.as_tensor(np.asarray(cols), device=Y.device)]
     errs = assert_y_close(Ysel, Y64, spec.name)
     return Y, Y64, errs
 
@@ -172,6 +175,45 @@ def _run_mx(spec, rows=None, s_begin=0, with_R=True, coltiles=0):
 ])
 def test_mx_layer_small_shapes(in_dtype, out_dtype, M, K, N, r):
     _run_mx(_spec(M, K, N, r, in_dtype=in_dtype, out_dtype=out_dtype))
+
+
+@pytest.mark.parametrize("in_dtype,out_dtype", [("bf16", "bf16"), ("fp16", "fp32")])
+@pytest.mark.parametrize("M,K,N,r", [
+    (1, 64, 32, 32),        # one fragment
+    (3, 192, 96, 32),       # a partial scale tile
+    (32, 1088, 288, 128),   # 17 fragments: ragged last group
+    (5, 320, 64, 96),       # odd fragment counts in both sequences
+    (17, 2048, 64, 256),    # 8 waves, groups of 4
+    (8, 4096, 128, 128),    # 8 waves, groups of 8
+    (32, 2560, 96, 320),    # 5 compensation fragments on 8 waves
+    (2, 8192, 64, 0),       # no compensation matrix
+])
+def test_mx_layer_decode_kernel(in_dtype, out_dtype, M, K, N, r):
+    _run_mx(_spec(M, K, N, r, in_dtype=in_dtype, out_dtype=out_dtype), path=serq.PATH_SKINNY)
+
+
+def test_mx_decode_kernel_offset_and_paths_agree():
+    _run_mx(_spec(7, 1024, 96, 64, out_dtype="fp32"), s_begin=512, path=serq.PATH_SKINNY)
+    # the two kernels on the same decode-sized call: same sums up to fp32 reordering
+    spec = _spec(20, 1536, 160, 128, out_dtype="fp32")
+    Ya, Y64, _ = _run_mx(spec, path=serq.PATH_SKINNY)
+    Yb, _, _ = _run_mx(spec, path=serq.PATH_MFMA)
+    assert np.max(np.abs(Ya.cpu().numpy() - Yb.cpu().numpy())) <= 1e-5 * np.max(np.abs(Y64))
+    # run-to-run identical
+    Yc, _, _ = _run_mx(spec, path=serq.PATH_SKINNY)
+    assert torch.equal(Ya, Yc)
+
+
+@pytest.mark.parametrize("which,M", [("up", 1), ("up", 16), ("down", 1), ("down", 16)])
+def test_mx_config3_decode(which, M):
+    _run_mx(workloads.config3(which, M))
+
+
+@pytest.mark.parametrize("M", [1, 32])
+def test_mx_config4_decode_sampled_channels(M):
+    spec = workloads.config4(M)
+    cols = np.sort(np.random.default_rng(5).choice(spec.N, size=1024, replace=False))
+    _run_mx(spec, cols=cols)
 
 
 def test_mx_layer_compensation_matters_and_can_be_left_out():
@@ -236,6 +278,9 @@ def test_mx_error_codes():
     with pytest.raises(serq.SerqError) as e:                       # missing scales
         serq.mx_linear(Xq, xsc, Wq, None, 64, 64, 512)
     assert e.value.code == -1
+    with pytest.raises(serq.SerqError) as e:                       # the streaming kernel takes at most 32 tokens
+        serq.mx_linear(Xq, xsc, Wq, wsc, 64, 64, 512, flags_=serq.flags(serq.PATH_SKINNY))
+    assert e.value.code == -3
     assert serq.lib().serq_mx_act_scale_bytes(3, 320) == 2 * 4 * 8
     assert serq.lib().serq_mx_weight_scale_bytes(64, 320) == 2 * 2 * 256
     assert serq.lib().serq_mx_weight_scale_bytes(48, 320) == 0
