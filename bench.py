@@ -413,6 +413,28 @@ def sweep():
         if small:
             b = decode_bytes(spec)
             row.update({"bound": "hbm", "gbs": round(b / l_us / 1e3, 1), "frac": round(b / l_us / 1e3 / HBM_PEAK_GBS, 4)})
+            # the same call in MXFP4 (weight-streaming kernel on the FP4 units), weights rotated the same way
+            rm = 32 * (r // 32)
+            Lw = workloads.make_layer(spec, want=("s", "W"))
+            mpk = serq.mx_pack_weights(Lw["W"].to(dev), Lw["s"].to(dev), rm, perm_in=pk.perm)
+            del Lw
+            per_copy = mpk.Wq.numel() + mpk.wsc.numel()
+            mcopy = int(np.ceil(640e6 / per_copy))
+            mW = [(mpk.Wq, mpk.wsc, mpk.Rq, mpk.rsc)] + [
+                (mpk.Wq.clone(), mpk.wsc.clone(), None if mpk.Rq is None else mpk.Rq.clone(),
+                 None if mpk.rsc is None else mpk.rsc.clone()) for _ in range(mcopy - 1)]
+            Xq4, xsc = serq.mx_quantize_act(Xhat, mpk.s_inv)
+
+            def mlin_d(i):
+                wq, wsc_, rq, rsc_ = mW[i % mcopy]
+                serq.mx_linear(Xq4, xsc, wq, wsc_, M, N, K, Rq=rq, rsc=rsc_, r=rm, Y=Y)
+
+            mlin_d(0)
+            md_us = _time_launches(mlin_d, max(20, 2 * mcopy), graph=True)
+            mb = N * K / 2 + N * K / 32 + (N * 64 * ((rm + 63) // 64) * (0.5 + 1 / 32) if rm else 0) + M * K / 2 + M * K / 32 + 2.0 * M * N
+            row["mxfp4"] = {"r": rm, "serq_mx_linear_us": round(md_us, 2), "bytes": int(mb), "gbs": round(mb / md_us / 1e3, 1),
+                            "frac_hbm_peak": round(mb / md_us / 1e3 / HBM_PEAK_GBS, 4)}
+            del mW, mpk
         else:
             ops = 2.0 * M * N * K
             row.update({"bound": "mfma", "tops": round(ops / l_us / 1e6, 1),
