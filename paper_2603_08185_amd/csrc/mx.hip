@@ -6,7 +6,8 @@
 // channels share one E8M0 scale 2^(E-127) with E - 127 = max(floor(log2(max|v|)) - 2, -127) (127 for
 // an all-zero block); elements are E2M1 codes (sign bit 8, magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6),
 // round to nearest with ties to the even mantissa bit, magnitudes above 6 saturating.  Scaling by a
-// power of two is exact in fp32, so every code is decided by exact comparisons.
+// power of two is exact in fp32, so every code is decided exactly: by comparisons against the
+// midpoints (the offline pack) or by the part's conversion instruction (the online quantiser).
 //
 // Layouts: codes use the INT4 layouts (activations: [M][K/2] bytes, a dword = 8 consecutive
 // channels, byte j = channel j in the low and channel 4+j in the high nibble; weights: [N/32][K/64]
