@@ -481,6 +481,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the M=1 decode leg")
     ap.add_argument("--calibrate-copy", action="store_true", help="only run a plain 1 GiB device copy (counter calibration)")
+    ap.add_argument("--no-mx", action="store_true", help="skip the MXFP4 leg of the default run")
     ap.add_argument("--mx", nargs="?", const="up", default=None, choices=["up", "down"],
                     help="time the MXFP4 variant of the layer on the headline shape (up, default) or its down projection instead")
     ap.add_argument("--sweep", action="store_true", help="time every benchmark configuration (one JSON line per row) instead of the headline step")
@@ -529,6 +530,15 @@ def main():
         d = bench_decode(L, pk)
         d["frac_of_measured_read_peak"] = d["gbs_hbm"] / mp["read_gbs_decode_size"]
         out["decode"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in d.items()}
+    if not a.no_mx:
+        # the MXFP4 variant of the same layer (its own line with `--mx`): step, layer kernel, quantiser
+        mx = bench_mx(min(a.steps, 300), min(a.warmup, 30))
+        out["mxfp4"] = {"step_tflops": mx["value"], "ms_per_step": mx["ms_per_step"],
+                        "kernel": mx["roofline"]["kernel"], "kernel_ms": mx["roofline"]["kernel_ms"],
+                        "kernel_tflops": mx["roofline"]["achieved"], "frac_of_fp4_peak": mx["roofline"]["frac"],
+                        "frac_of_measured_mfma_peak": mx["roofline"]["frac_of_measured_mfma_peak"],
+                        "mfma_fp4_tflops_measured": mx["measured_peaks"]["mfma_fp4_tflops"],
+                        "quantize_act_ms": mx["quantize_act"]["ms"]}
     if not a.no_cpu:
         cb, _ = cpu_baseline(L)
         cb["value"] = round(cb["value"], 5)
