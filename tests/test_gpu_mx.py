@@ -261,6 +261,14 @@ def test_mx_config3_up_M4096_sampled_rows():
     _run_mx(spec, rows=rows)
 
 
+def test_mx_config3_down_M4096_sampled_rows():
+    # the other shape `bench.py --mx down` times (one full round of 256 workgroups, 43 tiles deep)
+    spec = workloads.config3("down", 4096)
+    rows = np.sort(np.concatenate([np.random.default_rng(12).choice(4096, size=28, replace=False), [0, 4095]]))
+    rows = np.unique(rows)
+    _run_mx(spec, rows=rows)
+
+
 def test_mx_error_codes():
     Xq = torch.zeros(64 * 512 // 2, dtype=torch.uint8, device=DEV)
     xsc = torch.zeros(serq.lib().serq_mx_act_scale_bytes(64, 512), dtype=torch.uint8, device=DEV)
