@@ -55,6 +55,8 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, 8 TB/s
 # the runs and the arithmetic are in profiles/serq_mfma_kernel_cfg3_up_M4096_hbm_traffic.md.
 # 103 150 FETCH_SIZE counts x 2048 B + 88 088 WRITE_SIZE counts x 1024 B.
 LINEAR_TRAFFIC_BYTES = 103150 * 2048 + 88088 * 1024
+# the same two counters for serq_mx_kernel on the MXFP4 up projection: 78 736 and 88 098 counts
+MX_TRAFFIC_BYTES = 78736 * 2048 + 88098 * 1024
 
 
 def _events(n):
@@ -174,7 +176,7 @@ def bench_mx(steps: int, warmup: int, which: str = "up"):
                    "M": M, "K": K, "N": N, "r": r},
         "roofline": {"bound": "mfma", "kernel": "serq_mx_kernel (serq_mx_linear)", "achieved": round(tf_lin, 2),
                      "peak": FP4_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tf_lin / FP4_PEAK_TFLOPS, 4),
-                     "traffic": None, "kernel_ms": round(l_ms, 5),
+                     "traffic": MX_TRAFFIC_BYTES if which == "up" else None, "kernel_ms": round(l_ms, 5),
                      "frac_of_measured_mfma_peak": round(tf_lin / fp4_tf, 4)},
         "measured_peaks": {"mfma_fp4_tflops": round(fp4_tf, 1), "mfma_operands": "this layer's codes"},
         "quantize_act": {"ms": round(q_ms, 5), "gbs": round(qbytes / (q_ms * 1e-3) / 1e9, 1),
