@@ -35,20 +35,31 @@ __global__ __launch_bounds__(kT) void row_scale_kernel(const void* __restrict__ 
   }
 }
 
-// sal[k] = max_n |W[n,k]*s[k]|   (one thread per input channel, coalesced over k)
+__global__ __launch_bounds__(kT) void zero_floats_kernel(float* __restrict__ p, int n) {
+  const int i = blockIdx.x * kT + threadIdx.x;
+  if (i < n) p[i] = 0.0f;
+}
+
+// sal[k] = max_n |W[n,k]*s[k]|: a thread takes one input channel (coalesced over k) and a slab of
+// kSalRows output channels (blockIdx.y); the slabs meet in an integer maximum of the bit patterns,
+// which orders non-negative floats as the floats themselves and does not depend on the order of
+// arrival.  sal must be zero on entry.
+constexpr int kSalRows = 128;
 __global__ __launch_bounds__(kT) void col_saliency_kernel(const void* __restrict__ W, int w_dtype,
                                                           const float* __restrict__ s, int N, int K,
                                                           float* __restrict__ sal) {
   const int k = blockIdx.x * kT + threadIdx.x;
   if (k >= K) return;
   const float sk = s ? s[k] : 1.0f;
+  const int n0 = blockIdx.y * kSalRows;
+  const int n1 = n0 + kSalRows < N ? n0 + kSalRows : N;
   float m = 0.0f;
-  for (int n = 0; n < N; ++n) {
+  for (int n = n0; n < n1; ++n) {
     float w = ld_any(W, w_dtype, (size_t)n * K + k);
     if (s) w = w * sk;
     m = fmaxf(m, fabsf(w));
   }
-  sal[k] = m;
+  atomicMax(reinterpret_cast<unsigned int*>(sal) + k, __float_as_uint(m));
 }
 
 // Stable descending order by counting: position of k = number of channels that
@@ -264,14 +275,8 @@ int pack_weights_impl(const void* W, int w_dtype, const float* s, const int32_t*
                       void* Wq_out, float* wscale_out, int32_t* perm_out, float* s_inv_out, void* R_out,
                       int r_dtype, void* Rp_out, hipStream_t st) {
   hipLaunchKernelGGL(row_scale_kernel, dim3(N), dim3(kT), 0, st, W, w_dtype, s, K, wscale_out);
-  if (perm_in) {
-    hipLaunchKernelGGL(copy_perm_kernel, dim3(blocks_for(K)), dim3(kT), 0, st, perm_in, K, perm_out);
-  } else {
-    float* sal = s_inv_out;  // borrowed until sinv_kernel overwrites it
-    hipLaunchKernelGGL(col_saliency_kernel, dim3(blocks_for(K)), dim3(kT), 0, st, W, w_dtype, s, N, K, sal);
-    hipLaunchKernelGGL(rank_perm_kernel, dim3(blocks_for(K)), dim3(kT), 0, st, sal, K, perm_out);
-  }
-  hipLaunchKernelGGL(sinv_kernel, dim3(blocks_for(K)), dim3(kT), 0, st, s, perm_out, K, s_inv_out);
+  const int prc = prepare_perm_impl(W, w_dtype, s, perm_in, N, K, perm_out, s_inv_out, st);
+  if (prc != SERQ_OK) return prc;
   hipLaunchKernelGGL(quant_pack_kernel, dim3(blocks_for((size_t)N * K / 8)), dim3(kT), 0, st, W, w_dtype, s,
                      perm_out, wscale_out, N, K, (uint32_t*)Wq_out);
   if (r > 0 && (R_out || Rp_out)) {
@@ -288,7 +293,9 @@ int prepare_perm_impl(const void* W, int w_dtype, const float* s, const int32_t*
     hipLaunchKernelGGL(copy_perm_kernel, dim3(blocks_for(K)), dim3(kT), 0, st, perm_in, K, perm_out);
   } else {
     float* sal = s_inv_out;  // borrowed until sinv_kernel overwrites it
-    hipLaunchKernelGGL(col_saliency_kernel, dim3(blocks_for(K)), dim3(kT), 0, st, W, w_dtype, s, N, K, sal);
+    hipLaunchKernelGGL(zero_floats_kernel, dim3(blocks_for(K)), dim3(kT), 0, st, sal, K);
+    hipLaunchKernelGGL(col_saliency_kernel, dim3(blocks_for(K), (unsigned)((N + kSalRows - 1) / kSalRows)), dim3(kT), 0, st,
+                       W, w_dtype, s, N, K, sal);
     hipLaunchKernelGGL(rank_perm_kernel, dim3(blocks_for(K)), dim3(kT), 0, st, sal, K, perm_out);
   }
   hipLaunchKernelGGL(sinv_kernel, dim3(blocks_for(K)), dim3(kT), 0, st, s, perm_out, K, s_inv_out);
