@@ -15,8 +15,8 @@
 //
 // GLU variants: the token row is the gated product silu(gate) * up of two inputs (the input of the
 // down projection, quantised where it is made instead of being stored in 16 bits and read back;
-// Sec. 3.2, the decoder-layer flow of Fig. 2(b)).  The product is formed in fp32 (expf to an ulp, IEEE
-// division) and never rounded to the storage type.
+// Sec. 3.2, the decoder-layer flow of Fig. 2(b)).  The product is formed in fp32 (hardware exp2 and
+// reciprocal, an ulp each) and never rounded to the storage type.
 #include "serq_device.h"
 
 namespace serq {

@@ -67,8 +67,12 @@ __device__ __forceinline__ v4i as_v4i(const u4& p) { return __builtin_bit_cast(v
 // storage-type helpers -------------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
 __device__ __forceinline__ float f16_to_f32(uint16_t u) { return (float)__builtin_bit_cast(_Float16, u); }
-// silu(g) * u in fp32: expf to an ulp, IEEE division; g -> -inf gives -0 * u, g -> +inf gives g * u
-__device__ __forceinline__ float silu_mul(float g, float u) { return (g / (1.0f + expf(-g))) * u; }
+// silu(g) * u in fp32 with the hardware's exp2 and reciprocal (an ulp each, so the product is good to
+// a few ulps; the correctly rounded expf and an IEEE division made the fused quantisers VALU-bound);
+// g -> -inf gives g * 0 = -0, g -> +inf gives g * 1
+__device__ __forceinline__ float silu_mul(float g, float u) {
+  return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
+}
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   v2f x = {f, 0.0f};
