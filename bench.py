@@ -159,6 +159,23 @@ def bench_mx(steps: int, warmup: int, which: str = "up"):
     ops = 2.0 * M * N * K
     qbytes = 2.0 * M * K + M * K / 2 + M * K / 32
     tf_lin = ops / (l_ms * 1e-3) / 1e12
+    # the decode-sized call (M = 1) on the same weights, rotated over > 640 MB of copies, replayed from a graph
+    per_copy = pk.Wq.numel() + pk.wsc.numel()
+    ncopy = int(np.ceil(640e6 / per_copy))
+    copies = [(pk.Wq, pk.wsc, pk.Rq, pk.rsc)] + [(pk.Wq.clone(), pk.wsc.clone(), pk.Rq.clone(), pk.rsc.clone())
+                                                 for _ in range(ncopy - 1)]
+    Xq1, xsc1 = serq.mx_quantize_act(Xhat[:1].contiguous(), pk.s_inv)
+    Y1 = torch.empty((1, N), dtype=torch.bfloat16, device=dev)
+
+    def dec(i):
+        wq, wsc_, rq, rsc_ = copies[i % ncopy]
+        serq.mx_linear(Xq1, xsc1, wq, wsc_, 1, N, K, Rq=rq, rsc=rsc_, r=r, Y=Y1)
+
+    dec(0)
+    spin_up(lambda: dec(0), 0.05)
+    d_us = min(_time_launches(dec, 4 * ncopy, graph=True) for _ in range(3))
+    d_bytes = N * K / 2 + N * K / 32 + N * 64 * ((r + 63) // 64) * (0.5 + 1 / 32) + K / 2 + K / 32 + 2.0 * N
+    del copies
     # what the part sustains on nothing but FP4 MFMAs fed with this layer's own code bytes
     ops_buf = torch.cat([pk.Wq[:16384].reshape(256, 4, 16), Xq[:16384].reshape(256, 4, 16)], dim=1).contiguous()
     sink = torch.zeros(4, dtype=torch.int32, device=dev)
@@ -181,6 +198,9 @@ def bench_mx(steps: int, warmup: int, which: str = "up"):
         "measured_peaks": {"mfma_fp4_tflops": round(fp4_tf, 1), "mfma_operands": "this layer's codes"},
         "quantize_act": {"ms": round(q_ms, 5), "gbs": round(qbytes / (q_ms * 1e-3) / 1e9, 1),
                          "frac_hbm_peak": round(qbytes / (q_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "decode": {"workload": f"the same layer, M=1 (serq_skinny_mx_kernel), {ncopy} weight copies", "bytes": int(d_bytes),
+                   "us_hbm": round(d_us, 3), "gbs_hbm": round(d_bytes / d_us / 1e3, 1),
+                   "frac_hbm_peak": round(d_bytes / d_us / 1e3 / HBM_PEAK_GBS, 4)},
     }
 
 
@@ -540,7 +560,8 @@ def main():
                         "kernel_tflops": mx["roofline"]["achieved"], "frac_of_fp4_peak": mx["roofline"]["frac"],
                         "frac_of_measured_mfma_peak": mx["roofline"]["frac_of_measured_mfma_peak"],
                         "mfma_fp4_tflops_measured": mx["measured_peaks"]["mfma_fp4_tflops"],
-                        "quantize_act_ms": mx["quantize_act"]["ms"]}
+                        "quantize_act_ms": mx["quantize_act"]["ms"], "decode_M1_us": mx["decode"]["us_hbm"],
+                        "decode_M1_gbs": mx["decode"]["gbs_hbm"]}
     if not a.no_cpu:
         cb, _ = cpu_baseline(L)
         cb["value"] = round(cb["value"], 5)
