@@ -52,10 +52,6 @@ struct MxParams {
   int wide, nwide;
 };
 
-__device__ __forceinline__ v8i operand(const u4& v) {
-  const v4i q = as_v4i(v);
-  return __builtin_shufflevector(q, q, 0, 1, 2, 3, -1, -1, -1, -1);   // the FP4 forms read the first 16 bytes only
-}
 
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void serq_mx_kernel(const MxParams p) {
@@ -227,11 +223,11 @@ void serq_mx_kernel(const MxParams p) {
       fence();
       v8i xb[2];
 #pragma unroll
-      for (int j = 0; j < 2; ++j) xb[j] = operand(X[PAR][j]);
+      for (int j = 0; j < 2; ++j) xb[j] = fp4_operand(X[PAR][j]);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         if (i < NBW) {
-          const v8i wa = operand(W[i]);
+          const v8i wa = fp4_operand(W[i]);
 #pragma unroll
           for (int j = 0; j < 2; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wa, xb[j], acc[i][j], 4, 4, CHI, (int)ws[i],
@@ -307,11 +303,11 @@ void serq_mx_kernel(const MxParams p) {
       fence();
       v8i xb[2];
 #pragma unroll
-      for (int j = 0; j < 2; ++j) xb[j] = operand(X[0][j]);
+      for (int j = 0; j < 2; ++j) xb[j] = fp4_operand(X[0][j]);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         if (i < NBW) {
-          const v8i wa = operand(W[i]);
+          const v8i wa = fp4_operand(W[i]);
 #pragma unroll
           for (int j = 0; j < 2; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wa, xb[j], acc[i][j], 4, 4, 0, (int)ws[i], 0,

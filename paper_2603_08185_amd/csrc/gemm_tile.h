@@ -26,15 +26,7 @@ __device__ __forceinline__ void map_block(int bid, int tm, int tn, int gm, int& 
   tile_n = within / gsz;
 }
 
-// ---- direct-to-LDS loads and the hand-counted waits --------------------------
-__device__ __forceinline__ uint32_t lds_addr(const void* ptr) {
-  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)ptr;
-}
-// 16 bytes per lane: global (sbase + voff) -> LDS (lds_base_uniform + 16 * lane)
-__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base_uniform) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds_base_uniform), "v"(voff), "s"(sbase) : "memory", "m0");
-}
+// ---- the hand-counted waits of the direct-to-LDS loads (dma16, serq_device.h) ----------------
 // all but the youngest N vector-memory operations of this wave have completed,
 // this wave's LDS reads are complete, and every wave of the workgroup has got here
 template <int N>

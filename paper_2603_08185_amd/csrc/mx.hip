@@ -78,29 +78,6 @@ __device__ __forceinline__ uint32_t pack8(const uint32_t c[8]) {
 }
 
 // ---- activations ----------------------------------------------------------------------------------
-// 8 consecutive channels of a row, as fp32
-template <int XDT>
-__device__ __forceinline__ void load8(const char* row, int chunk, float v[8]) {
-  if constexpr (XDT == SERQ_F32) {
-    const float4* p = (const float4*)row + 2 * (size_t)chunk;
-    const float4 a = p[0], b = p[1];
-    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-  } else {
-    const uint4 u = ((const uint4*)row)[chunk];
-    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if constexpr (XDT == SERQ_BF16) {
-        v[2 * i] = __uint_as_float(w[i] << 16);
-        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-      } else {
-        v[2 * i] = f16_to_f32((uint16_t)(w[i] & 0xffffu));
-        v[2 * i + 1] = f16_to_f32((uint16_t)(w[i] >> 16));
-      }
-    }
-  }
-}
-
 // One workgroup per token; a thread owns 8 consecutive channels, four neighbouring threads a block.
 // (One 16-byte piece per thread on a two-dimensional grid, with the exponent bytes of a 256-channel
 // tile gathered by shuffles into one 8-byte store, measured 10 % slower.)

@@ -24,29 +24,6 @@ namespace {
 
 constexpr int kThreads = 256;
 
-template <int XDT>
-__device__ __forceinline__ void load8(const void* row, int chunk, float v[8]) {
-  if constexpr (XDT == SERQ_F32) {
-    const float4* p = (const float4*)row + 2 * (size_t)chunk;
-    float4 a = p[0], b = p[1];
-    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
-    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-  } else {
-    uint4 u = ((const uint4*)row)[chunk];
-    uint32_t w[4] = {u.x, u.y, u.z, u.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if constexpr (XDT == SERQ_BF16) {
-        v[2 * i] = __uint_as_float(w[i] << 16);
-        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-      } else {
-        v[2 * i] = f16_to_f32((uint16_t)(w[i] & 0xffffu));
-        v[2 * i + 1] = f16_to_f32((uint16_t)(w[i] >> 16));
-      }
-    }
-  }
-}
-
 // v <- silu(v) * u, elementwise
 template <int XDT>
 __device__ __forceinline__ void glu8(const void* urow, int chunk, float v[8]) {

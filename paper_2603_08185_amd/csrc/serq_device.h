@@ -74,6 +74,46 @@ __device__ __forceinline__ float silu_mul(float g, float u) {
   return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
 }
 
+// ---- helpers shared by several kernels -------------------------------------------------------------
+// LDS byte address of a pointer into shared memory
+__device__ __forceinline__ uint32_t lds_addr(const void* ptr) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)ptr;
+}
+// Direct global -> LDS load, 16 bytes per lane, no staging registers: global (sbase + voff) lands at
+// LDS (lds_base_uniform + 16 * lane).  Counted by hand with vmcnt by the callers.
+__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base_uniform) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_base_uniform), "v"(voff), "s"(sbase) : "memory", "m0");
+}
+// 16 bytes of E2M1 codes as an operand of the block-scaled MFMA (its FP4 forms read the first 16 bytes only)
+__device__ __forceinline__ v8i fp4_operand(const u4& v) {
+  const v4i q = as_v4i(v);
+  return __builtin_shufflevector(q, q, 0, 1, 2, 3, -1, -1, -1, -1);
+}
+// 8 consecutive channels (piece `chunk`) of a row stored as XDT, as fp32
+template <int XDT>
+__device__ __forceinline__ void load8(const void* row, int chunk, float v[8]) {
+  if constexpr (XDT == SERQ_F32) {
+    const float4* p = (const float4*)row + 2 * (size_t)chunk;
+    float4 a = p[0], b = p[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  } else {
+    uint4 u = ((const uint4*)row)[chunk];
+    uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if constexpr (XDT == SERQ_BF16) {
+        v[2 * i] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+      } else {
+        v[2 * i] = f16_to_f32((uint16_t)(w[i] & 0xffffu));
+        v[2 * i + 1] = f16_to_f32((uint16_t)(w[i] >> 16));
+      }
+    }
+  }
+}
+
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   v2f x = {f, 0.0f};
   v2bf y = __builtin_convertvector(x, v2bf);

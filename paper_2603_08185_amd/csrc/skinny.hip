@@ -85,14 +85,6 @@ __device__ __forceinline__ void finish(const SkinnyParams& p, int m, int n, int 
 
 constexpr int kRedPitch = 36;           // words per token row of a wave's parked partial sums
 
-__device__ __forceinline__ uint32_t lds_addr(const void* ptr) {
-  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)ptr;
-}
-// 16 bytes per lane, no staging registers: global (sbase + voff) -> LDS (lds_base_uniform + 16 * lane)
-__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base_uniform) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds_base_uniform), "v"(voff), "s"(sbase) : "memory", "m0");
-}
 
 // Geometry of the token staging for one group of kGroup consecutive fragments (4 or 8).
 template <int ABITS, int kGroup>

@@ -29,18 +29,6 @@ namespace {
 
 constexpr int kRedPitch = 36;           // words per token row of a wave's parked partial sums
 
-__device__ __forceinline__ uint32_t lds_addr(const void* ptr) {
-  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)ptr;
-}
-// 16 bytes per lane, no staging registers: global (sbase + voff) -> LDS (lds_base_uniform + 16 * lane)
-__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base_uniform) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds_base_uniform), "v"(voff), "s"(sbase) : "memory", "m0");
-}
-__device__ __forceinline__ v8i operand(const u4& v) {
-  const v4i q = as_v4i(v);
-  return __builtin_shufflevector(q, q, 0, 1, 2, 3, -1, -1, -1, -1);   // the FP4 forms read the first 16 bytes only
-}
 
 struct SkinnyMxParams {
   const uint8_t* Xq; const uint8_t* xsc;
@@ -137,7 +125,7 @@ __global__ __launch_bounds__(kWaves * 64) void serq_skinny_mx_kernel(const Skinn
         if (f0 + u < KB) {                              // uniform over the wave
           u4 xb = {0u, 0u, 0u, 0u};
           if (mv) xb = *(const u4*)(my + m * S::ROWB + (((2 * u + g) ^ S::sw(m)) << 4));
-          acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(operand(wp[u]), operand(xb), acc, 4, 4, u & 3,
+          acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fp4_operand(wp[u]), fp4_operand(xb), acc, 4, 4, u & 3,
                                                                 (int)wsd[u >> 2], u & 3, (int)xs[u >> 2]);
         }
       }
@@ -158,7 +146,7 @@ __global__ __launch_bounds__(kWaves * 64) void serq_skinny_mx_kernel(const Skinn
     const uint32_t xs = token_scales((p.s_begin >> 8) + (jf >> 2)) >> (8 * (jf & 3));
     u4 xb = {0u, 0u, 0u, 0u};
     if (mv) xb = *(const u4*)(p.Xq + (size_t)m * rowbytes + ((p.s_begin + 64 * jf) >> 1) + 16 * g);
-    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(operand(rq), operand(xb), acc, 4, 4, 0, (int)rs, 0, (int)xs);
+    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fp4_operand(rq), fp4_operand(xb), acc, 4, 4, 0, (int)rs, 0, (int)xs);
   }
 
   // ---- combine the waves ------------------------------------------------------------
