@@ -166,10 +166,11 @@ def bench_mx(steps: int, warmup: int, which: str = "up"):
                                                  for _ in range(ncopy - 1)]
     Xq1, xsc1 = serq.mx_quantize_act(Xhat[:1].contiguous(), pk.s_inv)
     Y1 = torch.empty((1, N), dtype=torch.bfloat16, device=dev)
+    ws1 = serq.mx_workspace(1, N, K, dev)
 
     def dec(i):
         wq, wsc_, rq, rsc_ = copies[i % ncopy]
-        serq.mx_linear(Xq1, xsc1, wq, wsc_, 1, N, K, Rq=rq, rsc=rsc_, r=r, Y=Y1)
+        serq.mx_linear(Xq1, xsc1, wq, wsc_, 1, N, K, Rq=rq, rsc=rsc_, r=r, Y=Y1, ws=ws1)
 
     dec(0)
     spin_up(lambda: dec(0), 0.05)
@@ -446,10 +447,11 @@ def sweep():
                 (mpk.Wq.clone(), mpk.wsc.clone(), None if mpk.Rq is None else mpk.Rq.clone(),
                  None if mpk.rsc is None else mpk.rsc.clone()) for _ in range(mcopy - 1)]
             Xq4, xsc = serq.mx_quantize_act(Xhat, mpk.s_inv)
+            mws = serq.mx_workspace(M, N, K, dev)
 
             def mlin_d(i):
                 wq, wsc_, rq, rsc_ = mW[i % mcopy]
-                serq.mx_linear(Xq4, xsc, wq, wsc_, M, N, K, Rq=rq, rsc=rsc_, r=rm, Y=Y)
+                serq.mx_linear(Xq4, xsc, wq, wsc_, M, N, K, Rq=rq, rsc=rsc_, r=rm, Y=Y, ws=mws)
 
             mlin_d(0)
             md_us = _time_launches(mlin_d, max(20, 2 * mcopy), graph=True)

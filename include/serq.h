@@ -209,8 +209,7 @@ int serq_gemm_i32(const void* Xq, int abits, const void* Wq,
  * second line, with Q = MXFP4), so the layer is
  *   Y[m,n] = sum_k X^[m,k] W^[n,k] + sum_{j<r} X^[m,s_begin+j] R^[n,j]
  * with no further scales.  It runs on the block-scaled FP4 matrix instructions, in a tiled kernel for
- * M > 32 and a weight-streaming kernel for M <= 32 (SERQ_PATH_* as for serq_linear; the streaming kernel
- * does not slice K and takes no workspace).
+ * M > 32 and a weight-streaming kernel for M <= 32 (SERQ_PATH_* as for serq_linear).
  *
  * Buffers (device memory, 16-byte aligned; opaque except through the unpack calls):
  *   activation codes  serq_packed_act_bytes(M,K,4) bytes
@@ -249,14 +248,23 @@ int serq_mx_unpack_weights(const void* Wq, const uint8_t* wscale, int64_t N, int
 int serq_mx_unpack_act(const void* Xq, const uint8_t* xscale, int64_t M, int64_t K,
                        uint8_t* codes_out, uint8_t* exps_out, void* stream);
 
+/* Bytes of workspace serq_mx_linear can use for this call (0: none).  Same rules as serq_workspace_bytes /
+ * serq_workspace_init: zero it once after allocation, the kernel leaves it zeroed; two calls that share a
+ * workspace must not overlap in time. */
+size_t serq_mx_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
 /* The MXFP4 layer.  Y [M,N] in y_dtype, row stride ldy (multiple of 8, >= N); fp32 accumulation over
  * k in the order of the hardware's 64-channel steps, the compensation sum added to the same
  * accumulators.  s_begin is a multiple of 256 with s_begin + 64*ceil(r/64) <= K; r a multiple of 32;
- * Rq may be NULL (no compensation).  flags: SERQ_PATH_* | SERQ_FLAG_COLTILES.  M = 0 is a no-op. */
+ * Rq may be NULL (no compensation).  workspace may be NULL: the decode kernel then never slices K; with
+ * it, layers with few blocks of 32 output channels and a long K are cut into K slices whose partial sums are
+ * added in a fixed order, so results do not vary from run to run, but they depend on the number of slices
+ * (fp32 addition).  flags: SERQ_PATH_* | SERQ_FLAG_SPLITK | SERQ_FLAG_COLTILES.  M = 0 is a no-op. */
 int serq_mx_linear(const void* Xq, const uint8_t* xscale, const void* Wq, const uint8_t* wscale,
                    int s_begin, int r, const void* Rq, const uint8_t* rscale,
                    int64_t M, int64_t N, int64_t K,
-                   void* Y, int y_dtype, int64_t ldy, int flags, void* stream);
+                   void* Y, int y_dtype, int64_t ldy,
+                   void* workspace, size_t workspace_bytes, int flags, void* stream);
 
 /*
  * Measuring sticks for benchmarks (no part of the layer; see the roofline discussion of Sec. 4.3's

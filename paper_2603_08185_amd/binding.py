@@ -52,7 +52,8 @@ SIGNATURES = {
     "serq_mx_pack_weights": (_i, [_vp, _i, _vp, _vp, _i64, _i64, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "serq_mx_unpack_weights": (_i, [_vp, _vp, _i64, _i64, _vp, _vp, _vp]),
     "serq_mx_unpack_act": (_i, [_vp, _vp, _i64, _i64, _vp, _vp, _vp]),
-    "serq_mx_linear": (_i, [_vp, _vp, _vp, _vp, _i, _i, _vp, _vp, _i64, _i64, _i64, _vp, _i, _i64, _i, _vp]),
+    "serq_mx_workspace_bytes": (_sz, [_i64, _i64, _i64]),
+    "serq_mx_linear": (_i, [_vp, _vp, _vp, _vp, _i, _i, _vp, _vp, _i64, _i64, _i64, _vp, _i, _i64, _vp, _sz, _i, _vp]),
     "serq_bench_mfma_peak": (_i, [_vp, _i, _i, _vp, _vp]),
     "serq_bench_mfma_fp4_peak": (_i, [_vp, _i, _i, _vp, _vp]),
     "serq_bench_read": (_i, [_vp, _sz, _i, _vp, _vp]),
@@ -364,6 +365,14 @@ def mx_quantize_act(X: torch.Tensor, s_inv: Optional[torch.Tensor],
     return Xq, xsc
 
 
+def mx_workspace(M: int, N: int, K: int, device) -> torch.Tensor:
+    """A zeroed workspace for serq_mx_linear (K slicing of the decode kernel)."""
+    n = lib().serq_mx_workspace_bytes(M, N, K)
+    ws = torch.empty(max(n, 16), dtype=torch.uint8, device=device)
+    _check("serq_workspace_init", lib().serq_workspace_init(_ptr(ws), ws.numel(), _stream()))
+    return ws
+
+
 def mx_unpack_act(Xq: torch.Tensor, xsc: torch.Tensor, M: int, K: int):
     codes = torch.empty((M, K), dtype=torch.uint8, device=Xq.device)
     exps = torch.empty((M, K // 32), dtype=torch.uint8, device=Xq.device)
@@ -375,12 +384,13 @@ def mx_unpack_act(Xq: torch.Tensor, xsc: torch.Tensor, M: int, K: int):
 def mx_linear(Xq: torch.Tensor, xsc: torch.Tensor, Wq: torch.Tensor, wsc: torch.Tensor, M: int, N: int, K: int,
               Rq: Optional[torch.Tensor] = None, rsc: Optional[torch.Tensor] = None, r: int = 0, s_begin: int = 0,
               out_dtype: torch.dtype = torch.bfloat16, Y: Optional[torch.Tensor] = None,
-              flags_: int = 0) -> torch.Tensor:
+              ws: Optional[torch.Tensor] = None, flags_: int = 0) -> torch.Tensor:
     """serq_mx_linear: Y = deq(X) . deq(W)^T + deq(X)[:, S] . deq(R)^T on the block-scaled FP4 units."""
     if Y is None:
         Y = torch.empty((M, N), dtype=out_dtype, device=Xq.device)
     rc = lib().serq_mx_linear(_ptr(Xq), _ptr(xsc), _ptr(Wq), _ptr(wsc), s_begin, r, _ptr(Rq), _ptr(rsc), M, N, K,
-                              _ptr(Y), _DT[Y.dtype], Y.stride(0) if M > 0 else N, flags_, _stream())
+                              _ptr(Y), _DT[Y.dtype], Y.stride(0) if M > 0 else N,
+                              _ptr(ws), 0 if ws is None else ws.numel(), flags_, _stream())
     _check("serq_mx_linear", rc)
     return Y
 

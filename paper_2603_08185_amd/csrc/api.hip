@@ -322,10 +322,16 @@ int serq_mx_unpack_act(const void* Xq, const uint8_t* xscale, int64_t M, int64_t
   return mx_unpack_act_impl(Xq, xscale, M, (int)K, codes_out, exps_out, (hipStream_t)stream);
 }
 
+size_t serq_mx_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+  if (M < 0 || check_nk(N, K) != SERQ_OK) return 0;
+  return M <= 32 ? skinny_mx_workspace_bytes((int)N) : 0;
+}
+
 int serq_mx_linear(const void* Xq, const uint8_t* xscale, const void* Wq, const uint8_t* wscale,
                    int s_begin, int r, const void* Rq, const uint8_t* rscale,
                    int64_t M, int64_t N, int64_t K,
-                   void* Y, int y_dtype, int64_t ldy, int flags, void* stream) {
+                   void* Y, int y_dtype, int64_t ldy,
+                   void* workspace, size_t workspace_bytes, int flags, void* stream) {
   int rc = check_nk(N, K);
   if (rc != SERQ_OK) return rc;
   if (M < 0 || M > (1 << 24)) return SERQ_ESHAPE;
@@ -337,7 +343,7 @@ int serq_mx_linear(const void* Xq, const uint8_t* xscale, const void* Wq, const 
   if (!Xq || !xscale || !Wq || !wscale || !Y) return SERQ_ENULL;
   if (r > 0 && Rq && !rscale) return SERQ_ENULL;
   if ((ldy % 8) != 0 || !aligned16(Y) || !aligned16(Xq) || !aligned16(xscale) || !aligned16(Wq) ||
-      !aligned16(wscale) || !aligned16(Rq) || !aligned16(rscale))
+      !aligned16(wscale) || !aligned16(Rq) || !aligned16(rscale) || !aligned16(workspace))
     return SERQ_EALIGN;
   MxLinearArgs a{};
   a.Xq = (const uint8_t*)Xq; a.xsc = xscale; a.Wq = (const u4*)Wq; a.wsc = wscale;
@@ -345,6 +351,8 @@ int serq_mx_linear(const void* Xq, const uint8_t* xscale, const void* Wq, const 
   a.M = (int)M; a.N = (int)N; a.K = (int)K;
   a.Y = Y; a.y_dtype = y_dtype; a.ldy = ldy;
   a.coltiles = (flags >> 20) & 0x7ff;
+  a.splitk = (flags >> 8) & 0xff;
+  a.workspace = workspace; a.workspace_bytes = workspace_bytes;
   const int path = flags & 0xff;
   if (path != SERQ_PATH_AUTO && path != SERQ_PATH_SKINNY && path != SERQ_PATH_MFMA) return SERQ_EUNSUPPORTED;
   if (path == SERQ_PATH_SKINNY && M > 32) return SERQ_ESHAPE;

@@ -228,6 +228,8 @@ struct MxLinearArgs {
   int M, N, K;
   void* Y; int y_dtype; int64_t ldy;
   int coltiles;
+  int splitk;                       // decode kernel: K slices per channel block (0 = choose)
+  void* workspace; size_t workspace_bytes;
 };
 int launch_mx_quantize_act(const void* X, const void* U, int x_dtype, const float* s_inv, int64_t M, int K, int64_t ldx,
                            int64_t ldu, void* Xq, uint8_t* xsc, hipStream_t st);
@@ -237,6 +239,7 @@ int mx_unpack_weights_impl(const void* Wq, const uint8_t* wsc, int N, int K, uin
 int mx_unpack_act_impl(const void* Xq, const uint8_t* xsc, int64_t M, int K, uint8_t* codes, uint8_t* E, hipStream_t st);
 int launch_mx_linear(const MxLinearArgs& a, hipStream_t st);
 int launch_skinny_mx(const MxLinearArgs& a, hipStream_t st);
+size_t skinny_mx_workspace_bytes(int N);
 
 int pack_weights_impl(const void* W, int w_dtype, const float* s, const int32_t* perm_in, int N, int K, int r,
                       void* Wq_out, float* wscale_out, int32_t* perm_out, float* s_inv_out, void* R_out,

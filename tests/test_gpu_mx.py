@@ -134,7 +134,7 @@ def test_mx_pack_zero_rows_and_blocks():
 # ---------------------------------------------------------------------------
 # the layer
 # ---------------------------------------------------------------------------
-def _run_mx(spec, rows=None, s_begin=0, with_R=True, coltiles=0, path=serq.PATH_AUTO, cols=None):
+def _run_mx(spec, rows=None, s_begin=0, with_R=True, coltiles=0, path=serq.PATH_AUTO, cols=None, ws=False, splitk=0):
     L = workloads.make_layer(spec, want=("X", "s", "W"))
     pk_o = orc.mx_pack_weights(f32(L["W"]), L["s"].numpy(), spec.r)
     pk = serq.mx_pack_weights(L["W"].to(DEV), L["s"].to(DEV), spec.r)
@@ -150,7 +150,9 @@ def _run_mx(spec, rows=None, s_begin=0, with_R=True, coltiles=0, path=serq.PATH_
     use_R = with_R and spec.r > 0
     Y = serq.mx_linear(Xq, xsc, pk.Wq, pk.wsc, spec.M, spec.N, spec.K, Rq=pk.Rq if use_R else None,
                        rsc=pk.rsc if use_R else None, r=spec.r if use_R else 0, s_begin=s_begin,
-                       out_dtype=DT[spec.out_dtype], flags_=serq.flags(path, coltiles=coltiles))
+                       out_dtype=DT[spec.out_dtype],
+                       ws=serq.mx_workspace(spec.M, spec.N, spec.K, DEV) if ws else None,
+                       flags_=serq.flags(path, splitk=splitk, coltiles=coltiles))
     csel = slice(None) if cols is None else np.asarray(cols)         # oracle on a sample of the output channels
     Y64 = orc.mx_linear(Xc_o, Xe_o, pk_o["Wc"][csel], pk_o["We"][csel], pk_o["Rc"][csel] if use_R else None,
                         pk_o["Re"][csel] if use_R else None, s_begin=s_begin)
@@ -204,9 +206,41 @@ def test_mx_decode_kernel_offset_and_paths_agree():
     assert torch.equal(Ya, Yc)
 
 
-@pytest.mark.parametrize("which,M", [("up", 1), ("up", 16), ("down", 1), ("down", 16)])
-def test_mx_config3_decode(which, M):
-    _run_mx(workloads.config3(which, M))
+@pytest.mark.parametrize("which,M,ws", [("up", 1, False), ("up", 16, True), ("down", 1, True), ("down", 16, True),
+                                        ("down", 1, False)])
+def test_mx_config3_decode(which, M, ws):
+    # (a workspace may be given; these layers have too many channel blocks for K slicing to pay, so none happens)
+    _run_mx(workloads.config3(which, M), ws=ws)
+
+
+@pytest.mark.parametrize("M,K,N,r,splitk", [
+    (1, 512, 32, 32, 2),        # two slices of one scale tile each
+    (5, 1088, 96, 128, 3),      # 5 scale tiles over 3 slices (2, 2, 1), the last one partial
+    (32, 4096, 64, 128, 16),    # the most slices
+    (17, 2048, 160, 64, 5),     # 8 scale tiles over 5 slices
+    (8, 8192, 64, 256, 0),      # chosen by the library: 2 blocks on 256 CUs, 32 scale tiles -> 4 slices
+])
+def test_mx_decode_kernel_k_slices(M, K, N, r, splitk):
+    spec = _spec(M, K, N, r, out_dtype="fp32")
+    Ya, Y64, _ = _run_mx(spec, path=serq.PATH_SKINNY, ws=True, splitk=splitk)
+    Yb, _, _ = _run_mx(spec, path=serq.PATH_SKINNY, ws=True, splitk=splitk)
+    assert torch.equal(Ya, Yb)                                      # the slices are added in a fixed order
+    Y1, _, _ = _run_mx(spec, path=serq.PATH_SKINNY, ws=False)      # one slice: same sums up to fp32 reordering
+    assert np.max(np.abs(Ya.cpu().numpy() - Y1.cpu().numpy())) <= 1e-5 * np.max(np.abs(Y64))
+
+
+def test_mx_decode_workspace_is_left_clean():
+    spec = _spec(9, 2048, 96, 64, out_dtype="fp32")
+    L = workloads.make_layer(spec, want=("X", "s", "W"))
+    pk = serq.mx_pack_weights(L["W"].to(DEV), L["s"].to(DEV), spec.r)
+    Xq, xsc = serq.mx_quantize_act(L["X"].to(DEV), pk.s_inv)
+    ws = serq.mx_workspace(spec.M, spec.N, spec.K, DEV)
+    outs = []
+    for _ in range(3):                                              # the same workspace, call after call
+        outs.append(serq.mx_linear(Xq, xsc, pk.Wq, pk.wsc, spec.M, spec.N, spec.K, Rq=pk.Rq, rsc=pk.rsc, r=spec.r,
+                                   out_dtype=torch.float32, ws=ws, flags_=serq.flags(serq.PATH_SKINNY, splitk=4)))
+        assert not ws.any()
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
 
 
 @pytest.mark.parametrize("M", [1, 32])
@@ -286,6 +320,9 @@ def test_mx_error_codes():
     with pytest.raises(serq.SerqError) as e:                       # missing scales
         serq.mx_linear(Xq, xsc, Wq, None, 64, 64, 512)
     assert e.value.code == -1
+    with pytest.raises(serq.SerqError) as e:                       # K slices asked for without a workspace
+        serq.mx_linear(Xq[:8 * 256], xsc, Wq, wsc, 8, 64, 512, flags_=serq.flags(serq.PATH_SKINNY, splitk=2))
+    assert e.value.code == -5
     with pytest.raises(serq.SerqError) as e:                       # the streaming kernel takes at most 32 tokens
         serq.mx_linear(Xq, xsc, Wq, wsc, 64, 64, 512, flags_=serq.flags(serq.PATH_SKINNY))
     assert e.value.code == -3
