@@ -287,6 +287,31 @@ def test_mx_layer_extreme_scales():
     assert np.all(Y.cpu().numpy()[:, 5] == 0.0)
 
 
+@pytest.mark.parametrize("M,path", [(8, serq.PATH_SKINNY), (64, serq.PATH_MFMA)])
+@pytest.mark.parametrize("ex,ew", [(-125, 100), (-110, -16), (100, 20), (-60, 60)])
+def test_mx_layer_ends_of_the_exponent_range(M, path, ex, ew):
+    # block exponents at and near both ends of E8M0 (E = 0 .. 2 and E around 225) through the matrix unit
+    K, N = 512, 64
+    rng = np.random.default_rng(21)
+    X = np.ldexp(rng.standard_normal((M, K)), ex).astype(np.float32)
+    W = np.ldexp(rng.standard_normal((N, K)), ew).astype(np.float32)
+    perm = np.arange(K, dtype=np.int32)
+    pk_o = orc.mx_pack_weights(W, None, 64, perm=perm)
+    pk = serq.mx_pack_weights(torch.from_numpy(W).to(DEV), None, 64, perm_in=torch.from_numpy(perm).to(DEV))
+    _check_pack(pk, pk_o, N, K, 64)
+    Xc_o, Xe_o = orc.mx_quantize_act(X, None)
+    Xq, xsc = serq.mx_quantize_act(torch.from_numpy(X).to(DEV), None)
+    codes, exps = serq.mx_unpack_act(Xq, xsc, M, K)
+    assert np.array_equal(codes.cpu().numpy(), Xc_o) and np.array_equal(exps.cpu().numpy(), Xe_o)
+    if ex == -125:
+        assert Xe_o.min() <= 1                                       # the clipped end of the range is exercised
+    Y = serq.mx_linear(Xq, xsc, pk.Wq, pk.wsc, M, N, K, Rq=pk.Rq, rsc=pk.rsc, r=64, out_dtype=torch.float32,
+                       flags_=serq.flags(path))
+    Y64 = orc.mx_linear(Xc_o, Xe_o, pk_o["Wc"], pk_o["We"], pk_o["Rc"], pk_o["Re"])
+    assert np.max(np.abs(Y64)) > 0 and np.all(np.isfinite(Y.cpu().numpy()))
+    assert_y_close(Y, Y64, f"exponents {ex} {ew}")
+
+
 def test_mx_config3_up_M4096_sampled_rows():
     # the benchmark shape in the launch configuration bench.py's sweep times
     spec = workloads.config3("up", 4096)
