@@ -99,6 +99,61 @@ def test_argument_validation_precedes_any_launch():
     assert L.serq_workspace_init(None, 0, None) == 0
 
 
+def test_mx_and_fused_entry_points_validate_before_any_launch():
+    L = serq.lib()
+    buf = (ctypes.c_char * 4096)()
+    a = (ctypes.cast(buf, ctypes.c_void_p).value + 15) & ~15
+    p = ctypes.c_void_p(a)
+    odd = ctypes.c_void_p(a + 4)
+    # size queries
+    assert L.serq_mx_act_scale_bytes(4096, 4096) == 16 * 4096 * 8
+    assert L.serq_mx_act_scale_bytes(3, 320) == 2 * 4 * 8             # two 256-channel tiles, M rounded up to even
+    assert L.serq_mx_act_scale_bytes(1, 100) == 0
+    assert L.serq_mx_weight_scale_bytes(11008, 4096) == 344 * 16 * 256
+    assert L.serq_mx_weight_scale_bytes(48, 4096) == 0
+    assert L.serq_mx_workspace_bytes(1, 4096, 4096) == 128 * 1024 * 4 * 17
+    assert L.serq_mx_workspace_bytes(64, 4096, 4096) == 0                # the tiled kernel takes none
+    # mx_quantize_act / the fused quantisers
+    assert L.serq_mx_quantize_act(p, 7, None, 1, 64, 64, p, p, None) == -2
+    assert L.serq_mx_quantize_act(p, 2, None, 1, 96, 96, p, p, None) == -3
+    assert L.serq_mx_quantize_act(p, 2, None, 1, 128, 64, p, p, None) == -3       # ldx < K
+    assert L.serq_mx_quantize_act(p, 2, None, 1, 64, 68, p, p, None) == -4
+    assert L.serq_mx_quantize_act(None, 2, None, 1, 64, 64, p, p, None) == -1
+    assert L.serq_mx_quantize_act(p, 2, None, 1, 64, 64, p, odd, None) == -4
+    assert L.serq_mx_quantize_act(None, 2, None, 0, 64, 64, None, None, None) == 0
+    assert L.serq_swiglu_quantize_act(p, None, 2, None, 1, 64, 64, 64, 8, p, p, None) == -1
+    assert L.serq_swiglu_quantize_act(p, p, 2, None, 1, 64, 64, 32, 8, p, p, None) == -3   # ldu < K
+    assert L.serq_swiglu_quantize_act(p, p, 2, None, 1, 64, 64, 64, 3, p, p, None) == -2
+    assert L.serq_swiglu_quantize_act(None, None, 2, None, 0, 64, 64, 64, 8, None, None, None) == 0
+    assert L.serq_mx_swiglu_quantize_act(p, None, 2, None, 1, 64, 64, 64, p, p, None) == -1
+    assert L.serq_mx_swiglu_quantize_act(p, p, 9, None, 1, 64, 64, 64, p, p, None) == -2
+    # mx_pack_weights
+    assert L.serq_mx_pack_weights(None, 2, None, None, 64, 64, 0, p, p, p, p, None, None, None) == -1
+    assert L.serq_mx_pack_weights(p, 2, None, None, 64, 64, 16, p, p, p, p, p, p, None) == -3      # r not a multiple of 32
+    assert L.serq_mx_pack_weights(p, 2, None, None, 64, 64, 32, p, p, p, p, None, None, None) == -1  # r > 0 needs Rq / rscale
+    assert L.serq_mx_pack_weights(p, 2, None, None, 60, 64, 0, p, p, p, p, None, None, None) == -3
+    assert L.serq_mx_unpack_weights(p, p, 64, 60, p, p, None) == -3
+    assert L.serq_mx_unpack_act(p, p, 1, 60, p, p, None) == -3
+    # mx_linear
+    def lin(Xq=p, xs=p, Wq=p, ws_=p, s_begin=0, r=0, Rq=None, rs=None, M=1, N=64, K=512, Y=p, ydt=2, ldy=64, wsp=None,
+            wsb=0, fl=0):
+        return L.serq_mx_linear(Xq, xs, Wq, ws_, s_begin, r, Rq, rs, M, N, K, Y, ydt, ldy, wsp, wsb, fl, None)
+    assert lin(N=48) == -3
+    assert lin(K=96) == -3
+    assert lin(ydt=9) == -2
+    assert lin(r=48, Rq=p, rs=p) == -3                 # rank not a multiple of the block
+    assert lin(s_begin=128, r=32, Rq=p, rs=p) == -3    # salient block off the 256-channel tiles
+    assert lin(s_begin=256, r=320, Rq=p, rs=p) == -3   # past K
+    assert lin(r=32, Rq=p, rs=None) == -1
+    assert lin(ws_=None) == -1
+    assert lin(ldy=32) == -3
+    assert lin(ldy=68) == -4
+    assert lin(Y=odd) == -4
+    assert lin(M=64, fl=1) == -3                       # streaming kernel forced with M > 32
+    assert lin(fl=9) == -7
+    assert lin(M=0) == 0
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(serq, "_lib", None)
     monkeypatch.setattr(serq, "LIB_PATH", "/nonexistent/libserq.so")
