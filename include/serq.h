@@ -4,7 +4,11 @@
  * The library implements the online hot path of SERQ (saliency-aware low-rank
  * error reconstruction): per-token activation quantisation, the INT4-weight
  * integer GEMM, and the single rank-r compensation fused into the
- * dequantising epilogue, plus the offline weight preparation.
+ * dequantising epilogue, plus the offline weight preparation.  Variants
+ * declared further down: the compensation matrix on the INT4 grid
+ * (serq_pack_lowrank_q4), the whole layer in MXFP4 (serq_mx_*), and the
+ * quantisers fused into the producer of the down projection's input
+ * (serq_swiglu_quantize_act, serq_mx_swiglu_quantize_act).
  *
  * Conventions for every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller, 16-byte
