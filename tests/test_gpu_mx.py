@@ -174,6 +174,7 @@ def _run_mx(spec, rows=None, s_begin=0, with_R=True, coltiles=0, path=serq.PATH_
     (64, 832, 32, 256),     # a full low-rank tile
     (33, 1280, 64, 320),    # two low-rank tiles
     (512, 2048, 256, 128),  # the steady-state loop (8 full tiles)
+    (777, 2304, 1056, 96),  # four token tiles (ragged), 33 channel blocks over several column tiles, 9 K tiles
 ])
 def test_mx_layer_small_shapes(in_dtype, out_dtype, M, K, N, r):
     _run_mx(_spec(M, K, N, r, in_dtype=in_dtype, out_dtype=out_dtype))
