@@ -13,7 +13,8 @@
  * Conventions for every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller, 16-byte
  *     aligned.  The library allocates nothing and keeps no state between
- *     calls; all work is enqueued on `stream` (a hipStream_t passed as
+ *     calls (the number of compute units is asked of the runtime on every
+ *     call); all work is enqueued on `stream` (a hipStream_t passed as
  *     void*, NULL = the default stream) and returns without waiting.
  *   - Matrices are row-major.  X is [M tokens, K input channels]; W is
  *     [N output channels, K input channels]; R is [r, N]; Y is [M, N].
@@ -95,7 +96,11 @@ int serq_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
  *   perm_in  [K] int32, perm_in[kp] = original channel placed at permuted
  *            position kp; NULL = order by saliency: channel scale
  *            max_n |W[n,k]*s[k]|, descending, ties to the lower index.
- *            A caller-supplied perm_in must be a permutation (not checked).
+ *            A caller-supplied perm_in is TRUSTED input: it must be a
+ *            permutation of 0..K-1.  It is not checked; an index out of range
+ *            makes the preparation kernels read W and s out of bounds, a
+ *            repeated one silently drops a channel, and the call still
+ *            returns SERQ_OK (the same holds for serq_mx_pack_weights).
  *   Wq_out   serq_packed_weight_bytes(N,K) bytes.
  *   wscale_out [N] fp32: max_k |W~[n,k]| / 7 (1.0 for an all-zero row).
  *   perm_out [K] int32 (required; equals perm_in when that is given).
@@ -269,25 +274,6 @@ int serq_mx_linear(const void* Xq, const uint8_t* xscale, const void* Wq, const 
                    int64_t M, int64_t N, int64_t K,
                    void* Y, int y_dtype, int64_t ldy,
                    void* workspace, size_t workspace_bytes, int flags, void* stream);
-
-/*
- * Measuring sticks for benchmarks (no part of the layer; see the roofline discussion of Sec. 4.3's
- * latency tables only in so far as they say what "peak" means on this part).
- *
- * serq_bench_mfma_peak: `workgroups` x 4 waves each run `iters` x 16 int8 MFMAs (32x32x32) on operands
- *   held in registers: 2 * 32*32*32 * 16 * iters * 4 * workgroups integer operations and nothing else.
- *   operands: 32 KiB (256 threads x 8 x 16 bytes: 4 A and 4 B operand registers per thread), device memory;
- *   the achieved rate depends on these bytes.  sink: 4 bytes of device memory (never written in practice).
- * serq_bench_mfma_fp4_peak: the same loop with the block-scaled FP4 MFMA (32x32x64, E2M1 codes, block
- *   exponent 127): 2 * 32*32*64 * 16 * iters * 4 * workgroups operations.  Each 16-byte operand slot holds
- *   the 32 codes of one lane.
- * serq_bench_read: reads [src, src + bytes) once with 16-byte loads from `workgroups` workgroups and
- *   does nothing else.  bytes a multiple of 16.
- * All return SERQ_OK or a negative code; all only launch (asynchronous on `stream`).
- */
-int serq_bench_mfma_peak(const void* operands, int iters, int workgroups, void* sink, void* stream);
-int serq_bench_mfma_fp4_peak(const void* operands, int iters, int workgroups, void* sink, void* stream);
-int serq_bench_read(const void* src, size_t bytes, int workgroups, void* sink, void* stream);
 
 #ifdef __cplusplus
 }

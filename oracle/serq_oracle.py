@@ -24,9 +24,10 @@ main + compensation == Q(X) . [W_s ; deq(Q(W_r))]; for the 4-bit compensation
 matrix a hand-worked example, the integer-matrix reduction, the scale/2 bound
 and the reduction to `linear` with the dequantised matrix; for MXFP4 the value
 table and tie cases of the format, hand-worked blocks, the power-of-two
-invariance, the error bound of the grid and brute force; for the gated product a
-library routine, the odd-part identity, limits and the reductions to the plain
-quantisers.  No function is unpinned.
+invariance, the error bound of the grid, brute force and a hand-worked offline
+preparation; for the gated product a library routine, the odd-part identity,
+limits and the reductions to the plain quantisers; for the comparator
+`rel_errors` hand-made pairs with known values.  No function is unpinned.
 """
 from __future__ import annotations
 
@@ -357,18 +358,25 @@ def dequant_reference(X, s, W, r: int, abits: int, perm=None):
 
 
 def rel_errors(Y, Y64):
-    """The two error measures the parity tests use for Y.
+    """The two error measures the parity tests use for Y (the reading of "max relative error").
 
     global : max |Y - Y64| / max |Y64|
     mixed  : max over elements of |Y - Y64| / (|Y64| + rms(Y64))
+    Both are 0 for empty inputs.  Against an all-zero reference any non-zero difference is an
+    infinite relative error (and an exact match is 0).
     """
     Y = np.asarray(Y, np.float64)
+    Y64 = np.asarray(Y64, np.float64)
+    if Y64.size == 0:
+        return 0.0, 0.0
     d = np.abs(Y - Y64)
-    denom = float(np.max(np.abs(Y64))) if Y64.size else 1.0
-    rms = float(np.sqrt(np.mean(Y64 * Y64))) if Y64.size else 1.0
-    g = float(np.max(d)) / denom if Y64.size and denom > 0 else 0.0
-    mix = float(np.max(d / (np.abs(Y64) + rms))) if Y64.size and rms > 0 else 0.0
-    return g, mix
+    dmax = float(np.max(d))
+    denom = float(np.max(np.abs(Y64)))
+    rms = float(np.sqrt(np.mean(Y64 * Y64)))
+    if denom == 0.0:
+        e = 0.0 if dmax == 0.0 else float("inf")
+        return e, e
+    return dmax / denom, float(np.max(d / (np.abs(Y64) + rms)))
 
 
 def effective_weight_bits(K: int, N: int, r: int, group: int = 0, scale_bits: int = 16,

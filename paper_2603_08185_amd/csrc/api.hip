@@ -1,5 +1,6 @@
 // C ABI of the library: argument checking and dispatch only (see include/serq.h).
 #include "serq_device.h"
+#include "../../include/serq_bench.h"
 
 using namespace serq;
 

@@ -668,14 +668,7 @@ void serq_mfma_kernel(const MfmaParams p) {
 }  // namespace
 
 int launch_mfma(const LinearArgs& a, hipStream_t st) {
-  static int ncu = 0;
-  if (ncu == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-      n = 256;
-    ncu = n;
-  }
+  const int ncu = device_cu_count();
   MfmaParams p;
   p.Xq = a.Xq; p.scale = a.scale; p.Wq = a.Wq; p.wscale = a.wscale;
   p.Rp = a.Rp; p.r_dtype = a.r_dtype; p.s_begin = a.s_begin; p.r = a.Rp ? a.r : 0;

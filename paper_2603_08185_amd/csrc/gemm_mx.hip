@@ -417,14 +417,7 @@ void serq_mx_kernel(const MxParams p) {
 }  // namespace
 
 int launch_mx_linear(const MxLinearArgs& a, hipStream_t st) {
-  static int ncu = 0;
-  if (ncu == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-      n = 256;
-    ncu = n;
-  }
+  const int ncu = device_cu_count();
   MxParams p;
   p.Xq = a.Xq; p.xsc = a.xsc; p.Wq = a.Wq; p.wsc = a.wsc;
   p.Rq = a.Rq; p.rsc = a.rsc; p.s_begin = a.s_begin; p.r = a.Rq ? a.r : 0;

@@ -54,6 +54,9 @@ __device__ __forceinline__ float absmax8(const float v[8], float m) {
 // quotient's own rounding), so the two round to the same integer unless t lies within that distance
 // of a half-integer; only then (the ties of synthetic inputs, and about one piece in a hundred
 // otherwise) are the divisions carried out.  The margin used is 1.25 * 2^-22 max(|t|, 1) over the piece.
+// A token whose scale is tiny (below 1e-30, a wave-uniform test: the reciprocal of a subnormal scale is
+// not finite, and neither estimate above holds near the bottom of the exponent range) always takes the
+// divisions.
 // (The bookkeeping of this check -- four VALU operations per value -- costs about a tenth of the
 // kernel's time; the fallback itself is too rare to show.)
 // Clamping before rounding equals rounding before clamping for integer bounds, and adding
@@ -71,7 +74,7 @@ __device__ __forceinline__ void codes8(const float v[8], float sc, float rsc, ui
     maxd = fmaxf(maxd, fabsf(tc - (uf - kMagic)));
     maxt = fmaxf(maxt, fabsf(tc));
   }
-  if (0.5f - maxd < 2.98023223876953125e-07f * maxt) {
+  if (sc < 1e-30f || 0.5f - maxd < 2.98023223876953125e-07f * maxt) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       float t = rintf(v[i] / sc);          // IEEE division, then round-half-to-even

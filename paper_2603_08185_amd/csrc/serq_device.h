@@ -194,6 +194,16 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Number of compute units of the current device, asked on every call (the library keeps no state);
+// 256 if the runtime cannot say.
+inline int device_cu_count() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+    n = 256;
+  return n;
+}
+
 // ---------------------------------------------------------------------------
 // host-side launchers implemented in the individual .hip files
 // ---------------------------------------------------------------------------

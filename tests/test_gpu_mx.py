@@ -244,11 +244,10 @@ def test_mx_decode_workspace_is_left_clean():
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
 
 
-@pytest.mark.parametrize("M", [1, 32])
-def test_mx_config4_decode_sampled_channels(M):
-    spec = workloads.config4(M)
-    cols = np.sort(np.random.default_rng(5).choice(spec.N, size=1024, replace=False))
-    _run_mx(spec, cols=cols)
+@pytest.mark.parametrize("M", [1, 4, 32])
+def test_mx_config4_decode(M):
+    # every output channel of the wide decode layer against the oracle
+    _run_mx(workloads.config4(M))
 
 
 def test_mx_layer_compensation_matters_and_can_be_left_out():
@@ -313,20 +312,16 @@ def test_mx_layer_ends_of_the_exponent_range(M, path, ex, ew):
     assert_y_close(Y, Y64, f"exponents {ex} {ew}")
 
 
-def test_mx_config3_up_M4096_sampled_rows():
-    # the benchmark shape in the launch configuration bench.py's sweep times
-    spec = workloads.config3("up", 4096)
-    rows = np.random.default_rng(11).choice(4096, size=48, replace=False)
-    rows = np.sort(np.concatenate([rows, [0, 255, 256, 4095]]))
-    _run_mx(spec, rows=rows)
+@pytest.mark.parametrize("which", ["up", "down"])
+def test_mx_config3_M4096(which):
+    # the shapes `bench.py --mx` times, in the launch configuration it times: every token row and
+    # every output channel against the oracle
+    _run_mx(workloads.config3(which, 4096))
 
 
-def test_mx_config3_down_M4096_sampled_rows():
-    # the other shape `bench.py --mx down` times (one full round of 256 workgroups, 43 tiles deep)
-    spec = workloads.config3("down", 4096)
-    rows = np.sort(np.concatenate([np.random.default_rng(12).choice(4096, size=28, replace=False), [0, 4095]]))
-    rows = np.unique(rows)
-    _run_mx(spec, rows=rows)
+@pytest.mark.parametrize("which", ["up", "down"])
+def test_mx_config3_M256(which):
+    _run_mx(workloads.config3(which, 256))
 
 
 def test_mx_error_codes():

@@ -71,6 +71,28 @@ def test_quantize_act_edges():
     assert scale.numel() == 0
 
 
+@pytest.mark.parametrize("abits", [4, 8])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_quantize_act_tiny_scales(abits, dtype):
+    # tokens at the bottom of the exponent range: scales that are subnormal (the reciprocal of such a
+    # scale is not finite), barely normal, and ordinary ones in between; zeros inside every row
+    K = 256
+    g = torch.Generator().manual_seed(17)
+    base = torch.randn((8, K), generator=g)
+    base[:, ::7] = 0.0
+    mags = torch.tensor([1e-38, 3e-39, 2e-37, 1e-36, 1e-33, 1e-30, 1e-25, 1.0]).reshape(8, 1)
+    X = (base.double() * mags.double()).to(torch.float32).to(dtype)
+    s_inv = torch.ones(K)
+    s_inv[::2] = 0.5
+    for sv in (None, s_inv):
+        Xq_o, scale_o = orc.quantize_act(f32(X), None if sv is None else sv.numpy(), abits)
+        Xq, scale = serq.quantize_act(X.to(DEV), None if sv is None else sv.to(DEV), abits)
+        assert np.array_equal(scale.cpu().numpy().view(np.uint32), scale_o.view(np.uint32))
+        assert np.array_equal(serq.unpack_act(Xq, abits, 8, K).cpu().numpy(), Xq_o)
+        assert scale_o[0] < 2.0 ** -126 and np.abs(Xq_o[0]).max() == orc.qmax(abits)
+        assert len(np.unique(Xq_o[0])) > 4                                     # not collapsed onto +-qmax
+
+
 # ---------------------------------------------------------------------------
 # offline pack
 # ---------------------------------------------------------------------------
@@ -166,10 +188,10 @@ def test_gemm_i32_skinny(abits, M, N, K, splitk):
     assert torch.equal(got, again)
 
 
-# Decode kernel variants: 4/8/16 waves per workgroup; token slice staged in LDS (small M*K) or read per
-# lane (large M*K); slices longer than one batch of fragments per wave (K = 13312 with 16 waves).
+# Decode kernel variants: 4 or 8 waves per workgroup (0 = the library's choice), groups of 4 or 8 fragments,
+# slices longer than one group per wave (K = 13312).
 @pytest.mark.parametrize("abits", [4, 8])
-@pytest.mark.parametrize("waves", [4, 8, 16])
+@pytest.mark.parametrize("waves", [0, 4, 8])
 @pytest.mark.parametrize("M,N,K", [(1, 64, 4096), (4, 64, 13312), (16, 96, 4096), (32, 64, 2048), (32, 64, 8192),
                                    (7, 32, 832), (2, 32, 64)])
 def test_gemm_i32_skinny_wave_counts(abits, waves, M, N, K):
@@ -186,11 +208,11 @@ def test_gemm_i32_skinny_wave_counts(abits, waves, M, N, K):
 
 
 @pytest.mark.parametrize("abits", [4, 8])
-@pytest.mark.parametrize("waves", [4, 8, 16])
+@pytest.mark.parametrize("waves", [0, 4, 8])
 @pytest.mark.parametrize("M,K,N,r", [(1, 4096, 64, 128), (16, 2048, 96, 256), (32, 2048, 64, 128), (32, 8192, 64, 32),
                                      (3, 832, 32, 16)])
 def test_layer_skinny_wave_counts(abits, waves, M, K, N, r):
-    # rank-r partials beside (small M) and on top of (M = 32, 16 waves) the integer partials in LDS
+    # rank-r partials parked in LDS after the integer partials (M rows further), for every workgroup size
     spec = _small_spec(abits, M, K, N, r)
     _run_layer(spec, R_mode="random", path=serq.PATH_SKINNY, groupm=waves // 4, check_pack=False)
     _run_layer(spec, R_mode="random", path=serq.PATH_SKINNY, groupm=waves // 4, splitk=2, check_pack=False)
@@ -398,10 +420,10 @@ def test_config3_q4r(which, M):
     _run_layer_q4r(workloads.config3(which, M))
 
 
-def test_config3_q4r_M4096_sampled_rows():
-    rows = np.sort(np.random.default_rng(43).choice(4096, size=64, replace=False))
-    rows[0], rows[-1] = 0, 4095
-    _run_layer_q4r(workloads.config3("up", 4096), rows=rows)
+@pytest.mark.parametrize("which", ["up", "down"])
+def test_config3_q4r_M4096(which):
+    # the benchmark's launch with the 4-bit compensation matrix: every token row against the oracle
+    _run_layer_q4r(workloads.config3(which, 4096))
 
 
 @pytest.mark.parametrize("M", [1, 32])
@@ -428,12 +450,9 @@ def test_config3_mlp_pair(which, M):
 
 
 @pytest.mark.parametrize("which", ["up", "down"])
-def test_config3_mlp_pair_M4096_sampled_rows(which):
-    # full-size launch as the benchmark times it; the oracle evaluates 96 sampled tokens completely
-    spec = workloads.config3(which, 4096)
-    rows = np.sort(np.random.default_rng(42).choice(4096, size=96, replace=False))
-    rows[0], rows[-1] = 0, 4095
-    _run_layer(spec, rows=rows, check_pack=(which == "up"))
+def test_config3_mlp_pair_M4096(which):
+    # the launch the benchmark times: codes, scales, every INT32 accumulator and every output against the oracle
+    _run_layer(workloads.config3(which, 4096))
 
 
 @pytest.mark.parametrize("M", [1, 4, 32])
@@ -441,12 +460,60 @@ def test_config4_wide_decode(M):
     _run_layer(workloads.config4(M), check_pack=(M == 1))
 
 
-@pytest.mark.parametrize("layer,r", [("qkv", 32), ("o", 64), ("gate_up", 128), ("down", 256), ("o", 0)])
-def test_config5_block_stack_sampled_rows(layer, r):
-    spec = workloads.config5(layer, r)
-    rows = np.sort(np.random.default_rng(7).choice(4096, size=64, replace=False))
-    rows[0], rows[-1] = 0, 4095
-    _run_layer(spec, R_mode="random" if r else "none", rows=rows, check_pack=False)
+@pytest.mark.parametrize("layer", workloads.config5_layers())
+def test_config5_block_stack(layer):
+    # every (layer, rank) cell of the block stack, all 4096 token rows.  The weights, the activations and hence
+    # the codes and the INT32 sums do not depend on the rank: they are computed once per layer on both sides
+    # and reused across the rank sweep; the compensation matrix is drawn per rank.
+    spec0 = workloads.config5(layer, 0)
+    L = workloads.make_layer(spec0, want=("X", "s", "W"))
+    O = oracle_layer(spec0, L, R_mode="none")
+    M, N, K = spec0.M, spec0.N, spec0.K
+    pk = serq.pack_weights(L["W"].to(DEV), L["s"].to(DEV), 0, want_R=False, want_Rp=False)
+    assert np.array_equal(pk.perm.cpu().numpy(), O.pk["perm"])
+    assert np.array_equal(pk.wscale.cpu().numpy(), O.pk["wscale"])
+    Xq, scale = serq.quantize_act(O.Xhat.to(DEV), pk.s_inv, spec0.abits)
+    assert np.array_equal(serq.unpack_act(Xq, spec0.abits, M, K).cpu().numpy(), O.Xq)
+    assert np.array_equal(scale.cpu().numpy().view(np.uint32), O.scale.view(np.uint32))
+    acc_o = orc.gemm_i32(O.Xq, O.pk["Wq"])
+    acc = serq.gemm_i32(Xq, spec0.abits, pk.Wq, M, N, K)
+    assert torch.equal(acc.cpu(), torch.from_numpy(acc_o))
+    del acc
+    for r in (0, 32, 64, 128, 256):
+        print(f"  [cfg5] {layer} r={r}", flush=True)
+        spec = workloads.config5(layer, r)
+        R = workloads.make_layer(spec, want=("R",)).get("R")
+        Rp = serq.pack_lowrank(R.to(DEV)) if r else None
+        Y = serq.linear(Xq, scale, spec.abits, pk.Wq, pk.wscale, M, N, K, Rp=Rp, r=r, out_dtype=DT[spec.out_dtype])
+        Y64 = orc.linear(O.Xq, O.scale, O.pk["Wq"], O.pk["wscale"], f64(R) if r else None, acc=acc_o)
+        assert_y_close(Y, Y64, spec.name)
+        del Y, Y64
+
+
+def test_lowrank_term_alone_at_its_own_magnitude():
+    # Y(r) - Y(r = 0) in fp32 is the compensation term by itself: compared with the oracle's
+    # scale[m] * sum_j Xq[m,S_j] R[j,n] relative to THAT term's size, so a wrong rank-r product cannot hide
+    # behind the much larger main product.  Both kernels, both activation widths, an offset salient block.
+    for abits, M, path in ((4, 9, serq.PATH_SKINNY), (8, 32, serq.PATH_SKINNY), (4, 300, serq.PATH_MFMA),
+                           (8, 130, serq.PATH_MFMA)):
+        spec = _small_spec(abits, M, 1088, 288, 128, out_dtype="fp32")
+        L = workloads.make_layer(spec)
+        O = oracle_layer(spec, L)
+        pk = serq.pack_weights(L["W"].to(DEV), L["s"].to(DEV), 0, want_R=False, want_Rp=False)
+        Xq, scale = serq.quantize_act(O.Xhat.to(DEV), pk.s_inv, abits)
+        Rp = serq.pack_lowrank(L["R"].to(DEV))
+        fl = serq.flags(path, splitk=1)
+        for s_begin in (0, 64):
+            Yr = serq.linear(Xq, scale, abits, pk.Wq, pk.wscale, M, spec.N, spec.K, Rp=Rp, r=spec.r, s_begin=s_begin,
+                             out_dtype=torch.float32, flags_=fl)
+            Y0 = serq.linear(Xq, scale, abits, pk.Wq, pk.wscale, M, spec.N, spec.K, Rp=None, r=0,
+                             out_dtype=torch.float32, flags_=fl)
+            term = (Yr.double() - Y0.double()).cpu().numpy()
+            want = O.scale.astype(np.float64)[:, None] * orc.lowrank(O.Xq, f64(L["R"]), s_begin)
+            main = np.max(np.abs(f64(Y0)))
+            # the difference of two fp32 outputs carries their rounding: a few ulps of the main product
+            assert np.max(np.abs(term - want)) <= 1e-3 * np.max(np.abs(want)) + 4 * 2.0 ** -24 * main, (abits, M, s_begin)
+            assert np.max(np.abs(want)) > 0
 
 
 def test_split_k_is_deterministic_and_matches_unsplit():

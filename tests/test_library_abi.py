@@ -12,9 +12,14 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "serq.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(serq_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for h in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if not h.endswith(".h"):
+            continue
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names.update(re.findall(r"\b(serq_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_symbols_exported_and_bound():
@@ -22,7 +27,7 @@ def test_header_symbols_exported_and_bound():
     assert len(names) >= 14
     L = serq.lib()
     for n in names:
-        assert hasattr(L, n), f"{n} declared in include/serq.h but not exported"
+        assert hasattr(L, n), f"{n} declared in include/*.h but not exported"
         assert n in serq.SIGNATURES, f"{n} has no Python binding signature"
     assert sorted(serq.SIGNATURES) == names
 

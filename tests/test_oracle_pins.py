@@ -79,6 +79,30 @@ def test_rounding_is_half_to_even():
     assert Xq[0].tolist() == [7, 0, 2, 2, 0, -2, -2, 4, 4, -6, 6, -4]
 
 
+@pytest.mark.parametrize("abits", [4, 8])
+def test_quantiser_at_the_bottom_of_the_exponent_range(abits):
+    # a token whose values are k * 2^-140 (exact subnormals): the scale is itself subnormal and the codes
+    # follow from exact rational arithmetic
+    from fractions import Fraction
+    q = orc.qmax(abits)
+    ks = np.array([100, -100, 37, -1, 0, 64, 99, -50, 13, 7, 3, 51], dtype=np.int64)
+    X = np.ldexp(ks.astype(np.float64), -140).astype(np.float32)[None, :]
+    assert np.array_equal(np.ldexp(X.astype(np.float64), 140)[0], ks)          # nothing was lost
+    Xq, scale = orc.quantize_act(X, None, abits)
+    # scale = rne(100 * 2^-140 / q) to a multiple of 2^-149 = rne(51200 / q) * 2^-149
+    num = Fraction(100 * 512, q)
+    sc_int = int(num) + (1 if (num - int(num) > Fraction(1, 2) or (num - int(num) == Fraction(1, 2) and int(num) % 2)) else 0)
+    assert float(scale[0]) == float(np.ldexp(float(sc_int), -149))
+    want = []
+    for k in ks.tolist():
+        t = Fraction(k * 512, sc_int)                     # exact quotient; fp32 rounds it to 24 bits, far from any tie here
+        n = int(t + Fraction(1, 2)) if t >= 0 else -int(-t + Fraction(1, 2))
+        assert abs(abs(t - int(t)) - Fraction(1, 2)) > Fraction(1, 100000)      # fp32 resolves 2^-22 here
+        want.append(max(-q, min(q, n)))
+    assert Xq[0].tolist() == want
+    assert abs(int(Xq[0, 0])) == q
+
+
 def test_zero_token_and_zero_weight_row():
     X = np.zeros((2, 16), np.float32)
     X[1, 3] = -2.0
@@ -453,3 +477,52 @@ def test_swiglu_reductions_to_the_plain_quantisers():
     c1, s1 = orc.swiglu_quantize_act(g, u, s_inv, 8)
     c2, s2 = orc.swiglu_quantize_act(g, -u, s_inv, 8)
     assert np.array_equal(c1, -c2) and np.array_equal(s1, s2)
+
+
+def test_mx_pack_hand_worked_blocks():
+    # tests/golden/tiny_mx_pack.txt: two output channels, three blocks of 32 input channels, two of them
+    # salient, every code and exponent byte derived by hand; a wrong block offset between the weights'
+    # exponents and the residual, a swapped block or a dropped tie rule changes Rc / Re
+    g = _read_golden(os.path.join(HERE, "golden", "tiny_mx_pack.txt"))
+    W = g["W"].astype(np.float32)
+    pk = orc.mx_pack_weights(W, None, 64, perm=np.arange(96, dtype=np.int32))
+    assert np.array_equal(pk["Wc"], g["Wc"].astype(np.uint8))
+    assert np.array_equal(pk["We"], g["We"].astype(np.uint8))
+    assert np.array_equal(pk["Rc"], g["Rc"].astype(np.uint8))
+    assert np.array_equal(pk["Re"], g["Re"].astype(np.uint8))
+    assert np.all(pk["s_inv"] == 1.0)
+    # with one salient block only, the compensation matrix is the first block of the one above
+    pk1 = orc.mx_pack_weights(W, None, 32, perm=np.arange(96, dtype=np.int32))
+    assert np.array_equal(pk1["Rc"], g["Rc"].astype(np.uint8)[:, :32])
+    assert np.array_equal(pk1["Re"], g["Re"].astype(np.uint8)[:, :1])
+    # the residual the codes stand for, by hand: row 0 block 0 = (0 1 .5 -.25 -.1875 .25 -.25 0) rounded to
+    # the grid at exponent -2, i.e. 0 1 .5 -.25 -.25 .25 -.25 0
+    Rd = orc.mx_dequantize(pk["Rc"], pk["Re"])
+    assert np.array_equal(Rd[0, :8], [0, 1, 0.5, -0.25, -0.25, 0.25, -0.25, 0])
+    assert np.array_equal(Rd[1, :8] * 32, Rd[0, :8])
+    assert np.array_equal(Rd[0, 32:40] * 4, Rd[0, :8][::-1])
+
+
+def test_rel_errors_hand_made_pairs():
+    # reference 3 4 0 0: max 4, rms sqrt(25/4) = 2.5
+    Y64 = np.array([[3.0, 4.0], [0.0, 0.0]])
+    Y = np.array([[3.5, 4.0], [0.25, 0.0]])
+    g, mix = orc.rel_errors(Y, Y64)
+    assert g == 0.5 / 4.0                                    # largest difference over the largest reference
+    assert mix == max(0.5 / (3.0 + 2.5), 0.25 / (0.0 + 2.5))  # a near-zero output is held to the rms
+    assert orc.rel_errors(Y64, Y64) == (0.0, 0.0)
+    # a sign error on the largest element: twice its magnitude
+    g, mix = orc.rel_errors(np.array([[3.0, -4.0], [0.0, 0.0]]), Y64)
+    assert g == 2.0 and mix == 8.0 / 6.5
+    # the two measures disagree where they should: a small error on a small element of a wide-range row
+    ref = np.array([[1000.0, 1.0]])
+    g, mix = orc.rel_errors(np.array([[1000.0, 2.0]]), ref)
+    assert g == 1e-3 and abs(mix - 1.0 / (1.0 + np.sqrt(1000001.0 / 2))) < 1e-15
+    # empty and all-zero references
+    assert orc.rel_errors(np.zeros((0, 4)), np.zeros((0, 4))) == (0.0, 0.0)
+    assert orc.rel_errors(np.zeros((2, 2)), np.zeros((2, 2))) == (0.0, 0.0)
+    g, mix = orc.rel_errors(np.full((2, 2), 1e-30), np.zeros((2, 2)))
+    assert g == float("inf") and mix == float("inf")
+    # any float type in, same numbers out
+    g32, m32 = orc.rel_errors(Y.astype(np.float32), Y64)
+    assert (g32, m32) == orc.rel_errors(Y, Y64)
