@@ -543,6 +543,9 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "serq_mfma_kernel<8, 2> (serq_linear; W4A8, bf16 R)",
                      "achieved": round(pre["tops_linear"], 2), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
                      "frac": round(pre["tops_linear"] / INT8_PEAK_TOPS, 4), "traffic": LINEAR_TRAFFIC_BYTES,
+                     "traffic_source": "constant from profiles/serq_mfma_kernel_cfg3_up_M4096_hbm_traffic.md (two "
+                                       "rocprofv3 --pmc runs of this command, FETCH_SIZE then WRITE_SIZE, scaled by "
+                                       "--calibrate-copy); not measured in this run",
                      "kernel_ms": round(pre["linear_ms"], 5)},
         "quantize_act": {"ms": round(pre["quant_ms"], 5), "gbs": round(pre["quant_gbs"], 1),
                          "frac_hbm_peak": round(pre["quant_gbs"] / HBM_PEAK_GBS, 4)},

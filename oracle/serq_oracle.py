@@ -26,7 +26,9 @@ and the reduction to `linear` with the dequantised matrix; for MXFP4 the value
 table and tie cases of the format, hand-worked blocks, the power-of-two
 invariance, the error bound of the grid, brute force and a hand-worked offline
 preparation; for the gated product a library routine, the odd-part identity,
-limits and the reductions to the plain quantisers; for the comparator
+limits and the reductions to the plain quantisers; for the group-128 / asymmetric
+setting a hand-worked row, the reductions to the per-channel symmetric path, the
+dense matmul of the dequantised operands and the half-step bounds; for the comparator
 `rel_errors` hand-made pairs with known values.  No function is unpinned.
 """
 from __future__ import annotations
@@ -204,6 +206,122 @@ def linear_q4r(Xq, scale, Wq, wscale, Rq, rscale, s_begin: int = 0, acc=None) ->
     acc_r = lowrank_i32(Xq, Rq, s_begin)
     y = (np.asarray(wscale, np.float64)[None, :] * acc.astype(np.float64)
          + np.asarray(rscale, np.float64)[None, :] * acc_r.astype(np.float64))
+    return np.asarray(scale, np.float64)[:, None] * y
+
+
+# ---------------------------------------------------------------------------
+# The accuracy-table setting (Sec. 4.1, implementation details): weights quantised in
+# groups of 128 input channels (round-to-nearest, symmetric), activations per token with
+# round-to-nearest ASYMMETRIC integer quantisation.  The paper names the scheme and gives
+# no formulas; the arithmetic below is the usual min-max affine quantiser:
+#   range [lo, hi] widened to contain 0, scale = (hi - lo) / (2^n - 1),
+#   zero = rne(-lo / scale), code = clip(rne(v / scale) + zero, 0, 2^n - 1),
+#   v^ = scale * (code - zero).
+# Codes are returned re-centred (code - 2^(n-1), zero - 2^(n-1)) so that they fit the signed
+# containers of the symmetric path; the dequantised values are the same.
+# ---------------------------------------------------------------------------
+GROUP = 128
+
+
+def quantize_act_asym(X: np.ndarray, s_inv, abits: int):
+    """Per-token asymmetric quantisation of the flattened activations (Eq. 4, then Sec. 4.1).
+
+    All decisions in IEEE fp32, as for the symmetric quantiser:
+      lo = min(0, min_k v), hi = max(0, max_k v)
+      scale[m] = (hi - lo) / (2^n - 1)            (1.0 for an all-zero token)
+      z[m]     = rne(-lo / scale)                 (0 .. 2^n - 1)
+      c[m,k]   = clip(rne(v / scale) + z, 0, 2^n - 1)
+    Returns (Xq int8 [M,K] = c - 2^(n-1), scale fp32 [M], zero int32 [M] = z - 2^(n-1));
+    the token stands for scale * (Xq - zero).
+    """
+    v = flatten(X, s_inv)
+    M, K = v.shape
+    top = F32((1 << abits) - 1)
+    half = 1 << (abits - 1)
+    lo = np.minimum(np.min(v, axis=1), F32(0)).astype(F32) if K else np.zeros(M, F32)
+    hi = np.maximum(np.max(v, axis=1), F32(0)).astype(F32) if K else np.zeros(M, F32)
+    span = (hi - lo).astype(F32)
+    scale = np.where(span > 0, span / top, F32(1.0)).astype(F32)
+    z = np.rint((-lo / scale).astype(F32)).astype(F32)
+    t = np.rint((v / scale[:, None]).astype(F32)).astype(F32)
+    c = np.clip((t + z[:, None]).astype(F32), F32(0), top)
+    return (c - F32(half)).astype(np.int8), scale, (z - F32(half)).astype(np.int32)
+
+
+def group_scales(Wp: np.ndarray, group: int = GROUP) -> np.ndarray:
+    """One symmetric INT4 scale per output channel and group of `group` input channels (Eq. 1 per group),
+    stored in 16 bits as the paper's effective-bit-width accounting assumes (4 + 16/128 = 4.125 bits):
+      gscale[n,g] = fp16_rne(max_{k in g} |W^[n,k]| / 7), kept inside fp16's positive range
+      [2^-24, 65504]; 1.0 for an all-zero group.  Returned widened to fp32 [N, K/group].
+    """
+    Wp = np.asarray(Wp, dtype=F32)
+    N, K = Wp.shape
+    assert K % group == 0
+    amax = np.max(np.abs(Wp.reshape(N, K // group, group)), axis=2).astype(F32)
+    with np.errstate(over="ignore"):
+        g16 = (amax / F32(7)).astype(F32).astype(np.float16)
+    g = g16.astype(F32)
+    g = np.clip(g, F32(2.0 ** -24), F32(65504.0)).astype(F32)
+    return np.where(amax > 0, g, F32(1.0)).astype(F32)
+
+
+def pack_weights_grouped(W: np.ndarray, s, r: int, perm=None, group: int = GROUP):
+    """Offline preparation with group-wise weight scales (Eq. 4, Eq. 5; Eq. 1 per group of 128 channels).
+
+      W^        = (W * s)[:, perm]                         fp32, salient channels lead
+      gscale    = group_scales(W^)                         [N, K/128]
+      Wq[n,k]   = clip(rne(W^[n,k] / gscale[n, k//128]), -7, 7)
+      R[j,n]    = W^[n,j] - gscale[n, j//128] * Wq[n,j],  j < r   (fp64, exact residual)
+      wsum[n]   = sum_k gscale[n, k//128] * Wq[n,k]        (fp64; what a zero point multiplies)
+    Returns dict(Wq, gscale, wsum, perm, s_inv, R).
+    """
+    W = np.asarray(W, dtype=F32)
+    N, K = W.shape
+    s = np.ones(K, F32) if s is None else np.asarray(s, dtype=F32)
+    Wt = W * s[None, :]
+    perm = saliency_permutation(Wt) if perm is None else np.asarray(perm, dtype=np.int32)
+    assert sorted(perm.tolist()) == list(range(K)), "perm must be a permutation of the channels"
+    Wp = Wt[:, perm]
+    gs = group_scales(Wp, group)
+    gfull = np.repeat(gs, group, axis=1)
+    Wq = np.clip(np.rint((Wp / gfull).astype(F32)), -7, 7).astype(np.int8)
+    deq = gfull.astype(np.float64) * Wq.astype(np.float64)
+    R = (Wp[:, :r].astype(np.float64) - deq[:, :r]).T.copy()
+    return {"Wq": Wq, "gscale": gs, "wsum": deq.sum(axis=1), "perm": perm,
+            "s_inv": (F32(1.0) / s)[perm].astype(F32), "R": R}
+
+
+def gemm_i32_grouped(Xq: np.ndarray, Wq: np.ndarray, group: int = GROUP) -> np.ndarray:
+    """acc[g,m,n] = sum_{k in group g} Xq[m,k] * Wq[n,k], exact: the integer GEMM of Eq. 2 cut at the
+    group boundaries, because every group is dequantised with its own scale."""
+    M, K = Xq.shape
+    N = Wq.shape[0]
+    G = K // group
+    out = np.empty((G, M, N), dtype=np.int32)
+    for g in range(G):
+        out[g] = gemm_i32(Xq[:, g * group:(g + 1) * group], Wq[:, g * group:(g + 1) * group])
+    return out
+
+
+def linear_grouped(Xq, scale, zero, Wq, gscale, R=None, s_begin: int = 0, group: int = GROUP) -> np.ndarray:
+    """The layer with group-wise weight scales and asymmetric activations, in fp64 (Eq. 2 + Eq. 7, first line):
+
+      Y[m,n] = sum_k x^[m,k] w^[n,k] + sum_{j<r} x^[m,S_j] R[j,n],
+      x^[m,k] = scale[m] (Xq[m,k] - zero[m]),  w^[n,k] = gscale[n, k//128] Wq[n,k],
+
+    evaluated as the definition says: group by group for the integer part, the zero point as its own term.
+    `zero` may be None (symmetric codes)."""
+    M, K = Xq.shape
+    z = np.zeros(M, np.float64) if zero is None else np.asarray(zero, np.float64)
+    acc = gemm_i32_grouped(Xq, Wq, group).astype(np.float64)                 # [G, M, N]
+    gs = np.asarray(gscale, np.float64)                                      # [N, G]
+    y = np.einsum("gmn,ng->mn", acc, gs)
+    wq_sum = Wq.astype(np.float64).reshape(Wq.shape[0], K // group, group).sum(axis=2)   # [N, G]
+    y = y - z[:, None] * (gs * wq_sum).sum(axis=1)[None, :]
+    if R is not None and R.shape[0] > 0:
+        r = R.shape[0]
+        xs = Xq[:, s_begin:s_begin + r].astype(np.float64) - z[:, None]
+        y = y + xs @ np.asarray(R, np.float64)
     return np.asarray(scale, np.float64)[:, None] * y
 
 

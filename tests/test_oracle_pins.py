@@ -526,3 +526,123 @@ def test_rel_errors_hand_made_pairs():
     # any float type in, same numbers out
     g32, m32 = orc.rel_errors(Y.astype(np.float32), Y64)
     assert (g32, m32) == orc.rel_errors(Y, Y64)
+
+
+# ---------------------------------------------------------------------------
+# group-128 weight scales + asymmetric activations (the accuracy-table setting, Sec. 4.1)
+# ---------------------------------------------------------------------------
+def test_grouped_asym_hand_worked_layer():
+    g = _read_golden(os.path.join(HERE, "golden", "tiny_grouped_asym.txt"))
+    X, W = g["X"].astype(np.float32), g["W"].astype(np.float32)
+    Xq, scale, zero = orc.quantize_act_asym(X, None, 4)
+    assert np.array_equal(scale, g["scale"][0].astype(np.float32))
+    assert np.array_equal(zero, g["zero"][0].astype(np.int32))
+    assert np.array_equal(Xq, g["Xq"].astype(np.int8))
+    pk = orc.pack_weights_grouped(W, None, 2, perm=np.arange(256, dtype=np.int32))
+    assert np.array_equal(pk["gscale"], g["gscale"].astype(np.float32))
+    assert np.array_equal(pk["Wq"], g["Wq"].astype(np.int8))
+    assert np.array_equal(pk["R"], g["R"])
+    assert np.array_equal(pk["wsum"], g["wsum"][0])
+    assert np.array_equal(orc.linear_grouped(Xq, scale, zero, pk["Wq"], pk["gscale"], None), g["Y0"])
+    assert np.array_equal(orc.linear_grouped(Xq, scale, zero, pk["Wq"], pk["gscale"], pk["R"]), g["Y"])
+
+
+@pytest.mark.parametrize("abits", [4, 8])
+def test_asym_quantiser_bounds_and_nearest_grid_point(abits):
+    rng = np.random.default_rng(abits)
+    M, K = 12, 256
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    X[0] += 3.0                      # mostly positive
+    X[1] = np.abs(X[1]) + 0.5        # strictly positive: the range is widened down to 0
+    X[2] = -np.abs(X[2]) - 0.5       # strictly negative: widened up to 0
+    X[3] = 0.0                       # zero token
+    X[4, :] = 2.5                    # constant token
+    s_inv = rng.uniform(0.5, 2.0, K).astype(np.float32)
+    v = orc.flatten(X, s_inv).astype(np.float64)
+    Xq, scale, zero = orc.quantize_act_asym(X, s_inv, abits)
+    top, half = (1 << abits) - 1, 1 << (abits - 1)
+    c = Xq.astype(np.int64) + half
+    z = zero.astype(np.int64) + half
+    assert c.min() >= 0 and c.max() <= top and z.min() >= 0 and z.max() <= top
+    assert scale[3] == 1.0 and not (c[3] - z[3]).any()
+    lo, hi = np.minimum(v.min(axis=1), 0), np.maximum(v.max(axis=1), 0)
+    ok = hi > lo
+    assert np.allclose(scale[ok], ((hi - lo) / top)[ok], rtol=1e-6)
+    assert z[1] == 0 and z[2] == top                     # one-sided tokens: zero point at an end of the grid
+    xh = scale.astype(np.float64)[:, None] * (c - z[:, None])
+    # half a step everywhere, plus the half step the zero point's own rounding can shift the grid by at the ends
+    assert np.all(np.abs(xh - v) <= scale[:, None] * (1.0 + 1e-5))
+    inner = (c > 0) & (c < top)
+    assert np.all(np.abs(xh - v)[inner] <= (0.5 + 1e-5) * np.broadcast_to(scale[:, None], v.shape)[inner])
+    # brute force: no other code of the grid is closer (beyond fp32 rounding of the quotient)
+    grid = scale.astype(np.float64)[:, None, None] * (np.arange(top + 1)[None, None, :] - z[:, None, None])
+    best = np.min(np.abs(grid - v[:, :, None]), axis=2)
+    assert np.all(np.abs(xh - v) <= best + 1e-5 * scale[:, None])
+    # zero is on the grid
+    assert np.all(np.min(np.abs(grid), axis=2) == 0)
+
+
+def test_grouped_weights_bounds_and_16_bit_scales():
+    rng = np.random.default_rng(3)
+    N, K, r = 24, 512, 32
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    s = rng.uniform(0.5, 2.0, K).astype(np.float32)
+    pk = orc.pack_weights_grouped(W, s, r)
+    gs = pk["gscale"]
+    assert gs.shape == (N, K // 128)
+    assert np.array_equal(gs.astype(np.float16).astype(np.float32), gs)       # representable in 16 bits
+    Wp = (W * s[None, :])[:, pk["perm"]]
+    amax = np.abs(Wp.reshape(N, K // 128, 128)).max(axis=2)
+    assert np.allclose(gs[amax > 0], (amax / 7)[amax > 0], rtol=2.0 ** -11)
+    deq = np.repeat(gs, 128, axis=1).astype(np.float64) * pk["Wq"]
+    # half a step, except where the 16-bit scale came out below max/7 and the extreme value clips at 7
+    assert np.all(np.abs(deq - Wp) <= np.repeat(gs, 128, axis=1) * (0.5 + 2.0 ** -9))
+    assert np.abs(pk["Wq"]).max() == 7
+    assert np.allclose(pk["R"], (Wp[:, :r] - deq[:, :r]).T, rtol=0, atol=0)
+    assert np.allclose(pk["wsum"], deq.sum(axis=1), rtol=1e-15)
+    # a zero group has scale 1 and zero codes
+    Wz = np.zeros((2, 256), np.float32)
+    Wz[0, 5] = 1.0
+    pz = orc.pack_weights_grouped(Wz, None, 0, perm=np.arange(256))
+    assert pz["gscale"].tolist() == [[np.float32(np.float16(1.0 / 7)), 1.0], [1.0, 1.0]] and not pz["Wq"][1].any()
+
+
+@pytest.mark.parametrize("abits", [4, 8])
+def test_grouped_reduces_to_the_per_channel_symmetric_path(abits):
+    # (a) equal group scales and no zero point: the grouped layer is the per-channel layer
+    rng = np.random.default_rng(11 + abits)
+    M, K, N, r = 5, 384, 6, 16
+    q = orc.qmax(abits)
+    Xq = rng.integers(-q, q + 1, size=(M, K)).astype(np.int8)
+    Wq = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
+    scale = rng.uniform(0.01, 0.1, M).astype(np.float32)
+    wscale = rng.uniform(0.001, 0.01, N).astype(np.float32)
+    R = rng.standard_normal((r, N)) * 0.01
+    a = orc.linear_grouped(Xq, scale, None, Wq, np.repeat(wscale[:, None], K // 128, axis=1), R)
+    b = orc.linear(Xq, scale, Wq, wscale, R)
+    assert np.allclose(a, b, rtol=1e-13, atol=1e-13)
+    assert np.array_equal(orc.gemm_i32_grouped(Xq, Wq).sum(axis=0), orc.gemm_i32(Xq, Wq))
+    # (b) the dense product of what the codes stand for, zero point included, salient block offset
+    zero = rng.integers(-q - 1, q + 1, size=M).astype(np.int32)
+    gs = rng.uniform(0.001, 0.01, (N, K // 128)).astype(np.float32)
+    xh = scale.astype(np.float64)[:, None] * (Xq.astype(np.float64) - zero[:, None])
+    wh = np.repeat(gs, 128, axis=1).astype(np.float64) * Wq
+    want = xh @ wh.T + xh[:, 128:128 + r] @ R
+    got = orc.linear_grouped(Xq, scale, zero, Wq, gs, R, s_begin=128)
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
+    # (c) one group spanning all of K with a scale that 16 bits hold exactly: the per-channel pack
+    W = rng.integers(-7, 8, size=(N, 128)).astype(np.float32) * np.float32(2.0 ** -6)
+    W[np.arange(N), rng.integers(0, 128, N)] = 7 * 2.0 ** -6
+    pg = orc.pack_weights_grouped(W, None, 16, perm=np.arange(128))
+    pc = orc.pack_weights(W, None, 16, perm=np.arange(128))
+    assert np.array_equal(pg["Wq"], pc["Wq"]) and np.array_equal(pg["gscale"][:, 0], pc["wscale"])
+    assert np.array_equal(pg["R"], pc["R"])
+    # (d) a symmetric token (lo = -hi) whose step is a power of two: the zero point sits at the exact tie
+    # (2^n - 1) / 2 -> 2^(n-1) by round-half-to-even, and the codes are the plain rounding on that step
+    top = (1 << abits) - 1
+    X = (rng.standard_normal((3, 256)) * 0.3).astype(np.float32)
+    X[:, 0] = top / 8.0
+    X[:, 1] = -top / 8.0
+    Xa, sa, za = orc.quantize_act_asym(X, None, abits)
+    assert np.all(za == 0) and np.all(sa == 0.25)
+    assert np.array_equal(Xa, np.clip(np.rint(X / np.float32(0.25)), -(top + 1) // 2, top // 2).astype(np.int8))
