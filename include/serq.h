@@ -49,6 +49,7 @@ extern "C" {
 #define SERQ_EWORKSPACE   -5   /* workspace missing or too small                */
 #define SERQ_EHIP         -6   /* the HIP runtime reported a launch error       */
 #define SERQ_EUNSUPPORTED -7   /* valid request this build does not implement   */
+#define SERQ_ELIMIT       -8   /* size beyond the built-in scratch of serq_linear_noalloc */
 
 /* element types of caller-visible tensors */
 #define SERQ_F32  0
@@ -198,6 +199,23 @@ int serq_linear(const void* Xq, const float* scale, int abits,
                 int64_t M, int64_t N, int64_t K,
                 void* Y, int y_dtype, int64_t ldy,
                 void* workspace, size_t workspace_bytes, int flags, void* stream);
+
+/*
+ * serq_linear for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, arithmetic and kernels as serq_linear, minus the
+ * workspace: the words in which the K slices of the decode path meet live in a device array inside the
+ * library (8 MiB per GPU, held until the process ends), so the call allocates nothing and asks the
+ * caller for nothing.  Limit: N <= 32768; beyond it the call returns SERQ_ELIMIT and does nothing.
+ * Results equal serq_linear's with a workspace, bit for bit.
+ * Every call on one GPU uses that GPU's one array: calls that overlap in time on the same GPU (two
+ * streams, two threads) race; calls on one stream, or otherwise ordered, are fine.  The kernels leave
+ * the array zeroed when they finish, so successive calls of any size need no clearing in between.
+ */
+int serq_linear_noalloc(const void* Xq, const float* scale, int abits,
+                        const void* Wq, const float* wscale,
+                        int s_begin, int r, const void* Rp, int r_dtype,
+                        int64_t M, int64_t N, int64_t K,
+                        void* Y, int y_dtype, int64_t ldy, int flags, void* stream);
 
 /* Parity aid: the same main loops, storing the raw INT32 accumulators
  * acc[m,n] = sum_k Xq[m,k]*Wq[n,k] (first term of Eq. 7) to acc_out [M,N],

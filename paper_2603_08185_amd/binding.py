@@ -45,6 +45,7 @@ SIGNATURES = {
     "serq_mx_swiglu_quantize_act": (_i, [_vp, _vp, _i, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
     "serq_linear": (_i, [_vp, _vp, _i, _vp, _vp, _i, _i, _vp, _i, _i64, _i64, _i64, _vp, _i, _i64,
                          _vp, _sz, _i, _vp]),
+    "serq_linear_noalloc": (_i, [_vp, _vp, _i, _vp, _vp, _i, _i, _vp, _i, _i64, _i64, _i64, _vp, _i, _i64, _i, _vp]),
     "serq_gemm_i32": (_i, [_vp, _i, _vp, _i64, _i64, _i64, _vp, _i64, _vp, _sz, _i, _vp]),
     "serq_mx_act_scale_bytes": (_sz, [_i64, _i64]),
     "serq_mx_weight_scale_bytes": (_sz, [_i64, _i64]),
@@ -281,6 +282,17 @@ def linear(Xq: torch.Tensor, scale: torch.Tensor, abits: int, Wq: torch.Tensor, 
                            Y.stride(0),
                            _ptr(ws), 0 if ws is None else ws.numel(), flags_, _stream())
     _check("serq_linear", rc)
+    return Y
+
+
+def linear_noalloc(Xq: torch.Tensor, scale: torch.Tensor, abits: int, Wq: torch.Tensor, wscale: torch.Tensor,
+                   M: int, N: int, K: int, Y: torch.Tensor, Rp: Optional[torch.Tensor] = None, r: int = 0,
+                   r_dtype=torch.bfloat16, s_begin: int = 0, flags_: int = 0) -> torch.Tensor:
+    """serq_linear_noalloc: serq_linear on the library's built-in scratch buffer; the caller passes Y."""
+    rc = lib().serq_linear_noalloc(_ptr(Xq), _ptr(scale), abits, _ptr(Wq), _ptr(wscale), s_begin, r, _ptr(Rp),
+                                   r_dtype if isinstance(r_dtype, int) else _DT[r_dtype], M, N, K, _ptr(Y),
+                                   _DT[Y.dtype], Y.stride(0), flags_, _stream())
+    _check("serq_linear_noalloc", rc)
     return Y
 
 

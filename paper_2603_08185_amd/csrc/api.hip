@@ -44,6 +44,7 @@ const char* serq_strerror(int code) {
     case SERQ_EWORKSPACE: return "workspace missing or too small";
     case SERQ_EHIP: return "HIP runtime error";
     case SERQ_EUNSUPPORTED: return "request not implemented";
+    case SERQ_ELIMIT: return "size beyond the built-in scratch buffer of the allocation-free entry point";
     default: return "unknown error code";
   }
 }

@@ -35,7 +35,7 @@ def test_header_symbols_exported_and_bound():
 def test_version_and_messages():
     L = serq.lib()
     assert L.serq_version() >= 100
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         assert len(L.serq_strerror(code)) > 0
     assert b"unknown" in L.serq_strerror(-99)
 
