@@ -293,6 +293,43 @@ int serq_mx_linear(const void* Xq, const uint8_t* xscale, const void* Wq, const 
                    void* Y, int y_dtype, int64_t ldy,
                    void* workspace, size_t workspace_bytes, int flags, void* stream);
 
+/*
+ * ---- The accuracy-table setting: group-128 weight scales, asymmetric activations ---------------------
+ * Sec. 4.1 (implementation details) runs the accuracy experiments with weights quantised in groups of
+ * 128 input channels (round-to-nearest symmetric INT4) and activations quantised per token with
+ * round-to-nearest ASYMMETRIC integers.  The paper gives no formulas; the arithmetic is the usual min-max
+ * affine quantiser:
+ *   token:   lo = min(0, min_k v), hi = max(0, max_k v), scale = (hi - lo) / (2^n - 1) (1.0 for a zero token),
+ *            z = rne(-lo / scale), c = clip(rne(v / scale) + z, 0, 2^n - 1), value = scale (c - z); all fp32.
+ *            Stored re-centred: Xq = c - 2^(n-1) in the containers of serq_quantize_act, zero = z - 2^(n-1).
+ *   weights: gscale[n,g] = fp16(max_{k in group g} |W~[n,k]| / 7) kept within [2^-24, 65504] (1.0 for a zero
+ *            group), Wq[n,k] = clip(rne(W~[n,k] / gscale[n, k/128]), -7, 7), value = gscale Wq.
+ *   layer:   Y[m,n] = sum_k x^[m,k] w^[n,k] + sum_{j<r} x^[m,s_begin+j] R[j,n]            (Eq. 2 + Eq. 7)
+ * with the integer sums of every group exact in INT32 and folded into fp32 group by group.
+ * K is a multiple of 128 here.  Weight codes have the layout of serq_pack_weights (serq_unpack_weights reads
+ * them back); the group scales take serq_g128_scale_bytes(N,K) bytes (opaque; serq_g128_unpack_scales gives
+ * fp32 [N, K/128]); wsum [N] fp32 = sum_k gscale[n,k/128] Wq[n,k], what a token's zero point multiplies.
+ */
+size_t serq_g128_scale_bytes(int64_t N, int64_t K);
+/* serq_quantize_act with the asymmetric grid above; zero_out [M] int32.  Everything else as serq_quantize_act. */
+int serq_quantize_act_asym(const void* X, int x_dtype, const float* s_inv, int64_t M, int64_t K, int64_t ldx, int abits,
+                           void* Xq_out, float* scale_out, int32_t* zero_out, void* stream);
+/* serq_pack_weights with one scale per output channel and group of 128 (permuted) input channels; s, perm_in,
+ * perm_out, s_inv_out, R_out, r_dtype, Rp_out as there (R = W~_s - gscale Wq over the r leading channels). */
+int serq_g128_pack_weights(const void* W, int w_dtype, const float* s, const int32_t* perm_in, int64_t N, int64_t K, int r,
+                           void* Wq_out, void* gscale_out, float* wsum_out, int32_t* perm_out, float* s_inv_out,
+                           void* R_out, int r_dtype, void* Rp_out, void* stream);
+int serq_g128_unpack_scales(const void* gscale, int64_t N, int64_t K, float* out, void* stream);
+/* The layer.  zero may be NULL (symmetric codes of serq_quantize_act: the same layer without zero points).
+ * Rp / r_dtype: the packed 16-bit compensation matrix as for serq_linear (r = 0 or NULL: none); s_begin a
+ * multiple of 32.  Y [M,N] in y_dtype, row stride ldy (multiple of 8).  flags: SERQ_PATH_* only (M <= 32 takes
+ * a weight-streaming kernel, larger M an LDS-tiled one).  fp32 sums are added in a fixed order: results do
+ * not vary from run to run.  No workspace. */
+int serq_g128_linear(const void* Xq, const float* scale, const int32_t* zero, int abits,
+                     const void* Wq, const void* gscale, const float* wsum,
+                     int s_begin, int r, const void* Rp, int r_dtype,
+                     int64_t M, int64_t N, int64_t K, void* Y, int y_dtype, int64_t ldy, int flags, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

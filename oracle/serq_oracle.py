@@ -312,12 +312,16 @@ def linear_grouped(Xq, scale, zero, Wq, gscale, R=None, s_begin: int = 0, group:
     evaluated as the definition says: group by group for the integer part, the zero point as its own term.
     `zero` may be None (symmetric codes)."""
     M, K = Xq.shape
+    N = Wq.shape[0]
     z = np.zeros(M, np.float64) if zero is None else np.asarray(zero, np.float64)
-    acc = gemm_i32_grouped(Xq, Wq, group).astype(np.float64)                 # [G, M, N]
     gs = np.asarray(gscale, np.float64)                                      # [N, G]
-    y = np.einsum("gmn,ng->mn", acc, gs)
-    wq_sum = Wq.astype(np.float64).reshape(Wq.shape[0], K // group, group).sum(axis=2)   # [N, G]
-    y = y - z[:, None] * (gs * wq_sum).sum(axis=1)[None, :]
+    y = np.zeros((M, N), np.float64)
+    wsum = np.zeros(N, np.float64)
+    for g in range(K // group):                                              # one exact integer GEMM per group
+        sl = slice(g * group, (g + 1) * group)
+        y += gemm_i32(Xq[:, sl], Wq[:, sl]).astype(np.float64) * gs[None, :, g]
+        wsum += gs[:, g] * Wq[:, sl].astype(np.float64).sum(axis=1)
+    y -= z[:, None] * wsum[None, :]
     if R is not None and R.shape[0] > 0:
         r = R.shape[0]
         xs = Xq[:, s_begin:s_begin + r].astype(np.float64) - z[:, None]

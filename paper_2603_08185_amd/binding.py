@@ -55,6 +55,11 @@ SIGNATURES = {
     "serq_mx_unpack_act": (_i, [_vp, _vp, _i64, _i64, _vp, _vp, _vp]),
     "serq_mx_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "serq_mx_linear": (_i, [_vp, _vp, _vp, _vp, _i, _i, _vp, _vp, _i64, _i64, _i64, _vp, _i, _i64, _vp, _sz, _i, _vp]),
+    "serq_g128_scale_bytes": (_sz, [_i64, _i64]),
+    "serq_quantize_act_asym": (_i, [_vp, _i, _vp, _i64, _i64, _i64, _i, _vp, _vp, _vp, _vp]),
+    "serq_g128_pack_weights": (_i, [_vp, _i, _vp, _vp, _i64, _i64, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp]),
+    "serq_g128_unpack_scales": (_i, [_vp, _i64, _i64, _vp, _vp]),
+    "serq_g128_linear": (_i, [_vp, _vp, _vp, _i, _vp, _vp, _vp, _i, _i, _vp, _i, _i64, _i64, _i64, _vp, _i, _i64, _i, _vp]),
     "serq_bench_mfma_peak": (_i, [_vp, _i, _i, _vp, _vp]),
     "serq_bench_mfma_fp4_peak": (_i, [_vp, _i, _i, _vp, _vp]),
     "serq_bench_read": (_i, [_vp, _sz, _i, _vp, _vp]),
@@ -423,3 +428,75 @@ def bench_mfma_fp4_peak(operands: torch.Tensor, iters: int, workgroups: int, sin
 def bench_read(src: torch.Tensor, nbytes: int, workgroups: int, sink: torch.Tensor) -> None:
     """serq_bench_read: nothing but one read of the first nbytes of src."""
     _check("serq_bench_read", lib().serq_bench_read(_ptr(src), nbytes, workgroups, _ptr(sink), _stream()))
+
+
+# ---- group-128 weight scales + asymmetric activations -------------------------------------------------
+@dataclass
+class G128PackedLayer:
+    """Device-resident artefacts of serq_g128_pack_weights for one layer."""
+    N: int
+    K: int
+    r: int
+    Wq: torch.Tensor        # uint8 blob (the layout of serq_pack_weights)
+    gscale: torch.Tensor    # uint8 blob: fp16 group scales
+    wsum: torch.Tensor      # fp32 [N]
+    perm: torch.Tensor
+    s_inv: torch.Tensor
+    R: Optional[torch.Tensor]
+    Rp: Optional[torch.Tensor]
+
+
+def g128_pack_weights(W: torch.Tensor, s: Optional[torch.Tensor], r: int, perm_in: Optional[torch.Tensor] = None,
+                      r_dtype: torch.dtype = torch.bfloat16) -> G128PackedLayer:
+    _dev(W, "W")
+    N, K = W.shape
+    L = lib()
+    nb = L.serq_g128_scale_bytes(N, K)
+    if nb == 0:
+        raise SerqError("serq_g128_scale_bytes", -3)
+    dev = W.device
+    Wq = torch.empty(N * K // 2, dtype=torch.uint8, device=dev)
+    gsc = torch.empty(nb, dtype=torch.uint8, device=dev)
+    wsum = torch.empty(N, dtype=torch.float32, device=dev)
+    perm = torch.empty(K, dtype=torch.int32, device=dev)
+    s_inv = torch.empty(K, dtype=torch.float32, device=dev)
+    R = torch.empty((r, N), dtype=r_dtype, device=dev) if r > 0 else None
+    Rp = torch.empty(L.serq_packed_lowrank_bytes(N, r), dtype=torch.uint8, device=dev) \
+        if r > 0 and r_dtype in (torch.float16, torch.bfloat16) else None
+    rc = L.serq_g128_pack_weights(_ptr(W), _DT[W.dtype], _ptr(s), _ptr(perm_in), N, K, r, _ptr(Wq), _ptr(gsc), _ptr(wsum),
+                                  _ptr(perm), _ptr(s_inv), _ptr(R), _DT[r_dtype], _ptr(Rp), _stream())
+    _check("serq_g128_pack_weights", rc)
+    return G128PackedLayer(N, K, r, Wq, gsc, wsum, perm, s_inv, R, Rp)
+
+
+def g128_unpack_scales(gscale: torch.Tensor, N: int, K: int) -> torch.Tensor:
+    out = torch.empty((N, K // 128), dtype=torch.float32, device=gscale.device)
+    _check("serq_g128_unpack_scales", lib().serq_g128_unpack_scales(_ptr(gscale), N, K, _ptr(out), _stream()))
+    return out
+
+
+def quantize_act_asym(X: torch.Tensor, s_inv: Optional[torch.Tensor], abits: int):
+    """serq_quantize_act_asym: returns (Xq packed uint8 blob, scale fp32 [M], zero int32 [M])."""
+    _rows(X, "X")
+    M, K = X.shape
+    L = lib()
+    Xq = torch.empty(max(L.serq_packed_act_bytes(M, K, abits), 16), dtype=torch.uint8, device=X.device)
+    scale = torch.empty(max(M, 1), dtype=torch.float32, device=X.device)[:M]
+    zero = torch.empty(max(M, 1), dtype=torch.int32, device=X.device)[:M]
+    rc = L.serq_quantize_act_asym(_ptr(X), _DT[X.dtype], _ptr(s_inv), M, K, X.stride(0) if M > 0 else K, abits,
+                                  _ptr(Xq), _ptr(scale), _ptr(zero), _stream())
+    _check("serq_quantize_act_asym", rc)
+    return Xq, scale, zero
+
+
+def g128_linear(Xq: torch.Tensor, scale: torch.Tensor, zero: Optional[torch.Tensor], abits: int, Wq: torch.Tensor,
+                gscale: torch.Tensor, wsum: torch.Tensor, M: int, N: int, K: int, Rp: Optional[torch.Tensor] = None,
+                r: int = 0, r_dtype: torch.dtype = torch.bfloat16, s_begin: int = 0,
+                out_dtype: torch.dtype = torch.bfloat16, Y: Optional[torch.Tensor] = None, flags_: int = 0) -> torch.Tensor:
+    """serq_g128_linear: the layer with group-128 weight scales and (optionally) per-token zero points."""
+    if Y is None:
+        Y = torch.empty((M, N), dtype=out_dtype, device=Xq.device)
+    rc = lib().serq_g128_linear(_ptr(Xq), _ptr(scale), _ptr(zero), abits, _ptr(Wq), _ptr(gscale), _ptr(wsum), s_begin, r,
+                                _ptr(Rp), _DT[r_dtype], M, N, K, _ptr(Y), _DT[Y.dtype], Y.stride(0), flags_, _stream())
+    _check("serq_g128_linear", rc)
+    return Y

@@ -1,0 +1,223 @@
+"""Parity of the group-128 / asymmetric-activation variant of the layer (through the C ABI) with the CPU oracle.
+
+Bit-exact: activation codes, scales and zero points; weight codes and 16-bit group scales; the permutation.
+Tolerance (max relative error, tests/_util.TOL): Y within 1e-3 for fp32 output and 1e-2 for bf16 / fp16 output.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import serq_oracle as orc
+from paper_2603_08185_amd import binding as serq
+from tests._util import DT, assert_y_close, f32, f64, ulp_close
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _spec(abits, M, K, N, r, in_dtype="bf16", out_dtype="bf16", seed_index=0):
+    return workloads.LayerSpec(f"g128_a{abits}_M{M}_K{K}_N{N}_r{r}", 9, abits, M, K, N, r, in_dtype, out_dtype, 3,
+                               20.0, 60.0, seed_index=seed_index)
+
+
+@pytest.mark.parametrize("abits", [4, 8])
+@pytest.mark.parametrize("dtype", ["bf16", "fp16", "fp32"])
+@pytest.mark.parametrize("M,K", [(1, 64), (7, 192), (33, 2048), (5, 4096), (3, 11008), (2, 16448)])
+def test_quantize_act_asym_bit_exact(abits, dtype, M, K):
+    L = workloads.make_layer(_spec(abits, M, K, 32, 0, in_dtype=dtype), want=("X", "s"))
+    X = L["X"] if dtype != "fp32" else L["X"].float()
+    s_inv = (np.float32(1.0) / L["s"].numpy()).astype(np.float32)
+    for sv in (s_inv, None):
+        Xq_o, sc_o, z_o = orc.quantize_act_asym(f32(X), sv, abits)
+        Xq, sc, z = serq.quantize_act_asym(X.to(DEV), None if sv is None else torch.from_numpy(sv).to(DEV), abits)
+        assert np.array_equal(sc.cpu().numpy().view(np.uint32), sc_o.view(np.uint32))
+        assert np.array_equal(z.cpu().numpy(), z_o)
+        assert np.array_equal(serq.unpack_act(Xq, abits, M, K).cpu().numpy(), Xq_o)
+
+
+def test_quantize_act_asym_edges():
+    # one-sided tokens (range widened to 0), a zero token, a constant token, ties, tiny magnitudes, strided rows
+    K = 256
+    g = torch.Generator().manual_seed(23)
+    X = torch.randn((9, K), generator=g)
+    X[0] = X[0].abs() + 0.5
+    X[1] = -X[1].abs() - 0.5
+    X[2] = 0.0
+    X[3] = 2.5
+    X[4] = (torch.arange(K) % 31 - 15).float() * 0.5          # halves on a grid of step 1: every tie
+    X[4, 0], X[4, 1] = 7.5, -7.5
+    X[5] *= 1e-38
+    X[6] *= 3e-36
+    X[7] *= 1e30
+    for abits in (4, 8):
+        for dt in (torch.float32, torch.bfloat16):
+            Xd = X.to(dt)
+            Xq_o, sc_o, z_o = orc.quantize_act_asym(f32(Xd), None, abits)
+            Xq, sc, z = serq.quantize_act_asym(Xd.to(DEV), None, abits)
+            assert np.array_equal(sc.cpu().numpy().view(np.uint32), sc_o.view(np.uint32)), (abits, dt)
+            assert np.array_equal(z.cpu().numpy(), z_o)
+            assert np.array_equal(serq.unpack_act(Xq, abits, 9, K).cpu().numpy(), Xq_o)
+    big = torch.randn((5, 2 * K), dtype=torch.bfloat16, generator=g)
+    Xq, sc, z = serq.quantize_act_asym(big.to(DEV)[:, :K], None, 4)
+    Xq_o, sc_o, z_o = orc.quantize_act_asym(f32(big[:, :K]), None, 4)
+    assert np.array_equal(serq.unpack_act(Xq, 4, 5, K).cpu().numpy(), Xq_o) and np.array_equal(z.cpu().numpy(), z_o)
+    e = torch.empty((0, K), dtype=torch.bfloat16, device=DEV)
+    assert serq.quantize_act_asym(e, None, 8)[1].numel() == 0
+
+
+def _check_pack(pk, pk_o, N, K, r, rdt):
+    assert np.array_equal(pk.perm.cpu().numpy(), pk_o["perm"])
+    assert np.array_equal(pk.s_inv.cpu().numpy().view(np.uint32), pk_o["s_inv"].view(np.uint32))
+    gs = serq.g128_unpack_scales(pk.gscale, N, K).cpu().numpy()
+    assert np.array_equal(gs.view(np.uint32), pk_o["gscale"].view(np.uint32))
+    assert np.array_equal(serq.unpack_weights(pk.Wq, N, K).cpu().numpy(), pk_o["Wq"])
+    mag = np.abs(np.repeat(pk_o["gscale"], 128, axis=1).astype(np.float64) * pk_o["Wq"]).sum(axis=1)
+    assert np.all(np.abs(pk.wsum.cpu().numpy().astype(np.float64) - pk_o["wsum"]) <= 2.0 ** -23 * mag + 1e-30)
+    if r:
+        assert ulp_close(f64(pk.R), pk_o["R"], rdt, ulps=1.0)
+        assert torch.equal(serq.unpack_lowrank(pk.Rp, N, r, rdt).view(torch.int16), pk.R.view(torch.int16))
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16", "fp32"])
+@pytest.mark.parametrize("N,K,r", [(32, 128, 16), (96, 384, 32), (256, 256, 16), (288, 1152, 144)])
+def test_g128_pack_weights_parity(dtype, N, K, r):
+    L = workloads.make_layer(_spec(4, 4, K, N, r, in_dtype=dtype), want=("W", "s"))
+    W = L["W"] if dtype != "fp32" else L["W"].float()
+    rdt = DT[dtype] if dtype != "fp32" else torch.bfloat16
+    pk_o = orc.pack_weights_grouped(f32(W), L["s"].numpy(), r)
+    pk = serq.g128_pack_weights(W.to(DEV), L["s"].to(DEV), r, r_dtype=rdt)
+    _check_pack(pk, pk_o, N, K, r, rdt)
+    perm = np.random.default_rng(1).permutation(K).astype(np.int32)
+    pk_o2 = orc.pack_weights_grouped(f32(W), None, 0, perm=perm)
+    pk2 = serq.g128_pack_weights(W.to(DEV), None, 0, perm_in=torch.from_numpy(perm).to(DEV))
+    _check_pack(pk2, pk_o2, N, K, 0, rdt)
+
+
+def test_g128_pack_zero_groups_and_scale_range():
+    N, K = 32, 384
+    W = torch.randn((N, K), generator=torch.Generator().manual_seed(4))
+    W[3, :] = 0.0
+    W[5, 128:256] = 0.0
+    W[7, :128] *= 1e-9            # group scale below fp16's smallest subnormal: held at 2^-24
+    W[9, 256:] *= 1e7             # above fp16's largest value: held at 65504
+    perm = np.arange(K, dtype=np.int32)
+    pk_o = orc.pack_weights_grouped(W.numpy(), None, 16, perm=perm)
+    pk = serq.g128_pack_weights(W.to(DEV), None, 16, perm_in=torch.from_numpy(perm).to(DEV), r_dtype=torch.float32)
+    gs = serq.g128_unpack_scales(pk.gscale, N, K).cpu().numpy()
+    assert np.array_equal(gs, pk_o["gscale"])
+    assert gs[3].tolist() == [1.0, 1.0, 1.0] and gs[5, 1] == 1.0 and gs[7, 0] == 2.0 ** -24 and gs[9, 2] == 65504.0
+    assert np.array_equal(serq.unpack_weights(pk.Wq, N, K).cpu().numpy(), pk_o["Wq"])
+
+
+def _run(spec, path=serq.PATH_AUTO, asym=True, R_mode="residual", s_begin=0):
+    L = workloads.make_layer(spec)
+    rdt = DT[spec.in_dtype]
+    pk_o = orc.pack_weights_grouped(f32(L["W"]), L["s"].numpy(), spec.r)
+    pk = serq.g128_pack_weights(L["W"].to(DEV), L["s"].to(DEV), spec.r, r_dtype=rdt)
+    _check_pack(pk, pk_o, spec.N, spec.K, spec.r, rdt)
+    Xhat = workloads.permute_channels(L["X"], pk_o["perm"])
+    if asym:
+        Xq_o, sc_o, z_o = orc.quantize_act_asym(f32(Xhat), pk_o["s_inv"], spec.abits)
+        Xq, sc, z = serq.quantize_act_asym(Xhat.to(DEV), pk.s_inv, spec.abits)
+        assert np.array_equal(z.cpu().numpy(), z_o)
+    else:
+        Xq_o, sc_o = orc.quantize_act(f32(Xhat), pk_o["s_inv"], spec.abits)
+        z_o = None
+        Xq, sc = serq.quantize_act(Xhat.to(DEV), pk.s_inv, spec.abits)
+        z = None
+    assert np.array_equal(sc.cpu().numpy().view(np.uint32), sc_o.view(np.uint32))
+    assert np.array_equal(serq.unpack_act(Xq, spec.abits, spec.M, spec.K).cpu().numpy(), Xq_o)
+    if spec.r == 0 or R_mode == "none":
+        Rp, R64, r = None, None, 0
+    elif R_mode == "random":
+        Rp, R64, r = serq.pack_lowrank(L["R"].to(DEV)), f64(L["R"]), spec.r
+    else:
+        Rp, R64, r = pk.Rp, f64(pk.R), spec.r             # the residual as the library stored it (checked above)
+    Y = serq.g128_linear(Xq, sc, z, spec.abits, pk.Wq, pk.gscale, pk.wsum, spec.M, spec.N, spec.K, Rp=Rp, r=r,
+                         r_dtype=rdt, s_begin=s_begin, out_dtype=DT[spec.out_dtype], flags_=serq.flags(path))
+    Y64 = orc.linear_grouped(Xq_o, sc_o, z_o, pk_o["Wq"], pk_o["gscale"], R64, s_begin=s_begin)
+    return Y, Y64, assert_y_close(Y, Y64, spec.name)
+
+
+@pytest.mark.parametrize("abits", [4, 8])
+@pytest.mark.parametrize("in_dtype,out_dtype", [("bf16", "bf16"), ("fp16", "fp32"), ("fp16", "fp16")])
+@pytest.mark.parametrize("M,K,N,r,path", [
+    (1, 128, 32, 16, serq.PATH_SKINNY),
+    (3, 384, 96, 16, serq.PATH_SKINNY),
+    (32, 1152, 288, 128, serq.PATH_SKINNY),
+    (5, 640, 64, 144, serq.PATH_SKINNY),
+    (17, 4096, 64, 64, serq.PATH_SKINNY),
+    (33, 128, 32, 16, serq.PATH_MFMA),
+    (40, 384, 96, 32, serq.PATH_MFMA),
+    (300, 1152, 288, 128, serq.PATH_MFMA),
+    (257, 512, 544, 64, serq.PATH_MFMA),
+    (130, 256, 160, 80, serq.PATH_MFMA),
+    (20, 1536, 160, 128, serq.PATH_MFMA),
+])
+def test_g128_layer_small_shapes(abits, in_dtype, out_dtype, M, K, N, r, path):
+    spec = _spec(abits, M, K, N, r, in_dtype=in_dtype, out_dtype=out_dtype)
+    _run(spec, path=path)
+    _run(spec, path=path, R_mode="random")
+
+
+@pytest.mark.parametrize("path,M", [(serq.PATH_SKINNY, 9), (serq.PATH_MFMA, 70)])
+def test_g128_layer_variants(path, M):
+    spec = _spec(8, M, 768, 96, 32, out_dtype="fp32")
+    _run(spec, path=path, asym=False)                       # symmetric codes, no zero points
+    _run(spec, path=path, R_mode="none")                    # no compensation matrix
+    _run(spec, path=path, R_mode="random", s_begin=160)     # salient block elsewhere
+    Ya, _, _ = _run(spec, path=path)
+    Yb, _, _ = _run(spec, path=path)
+    assert torch.equal(Ya, Yb)                              # fixed summation order
+
+
+def test_g128_zero_point_term_alone():
+    # a token shifted by a constant changes only its zero point's rank-one term: Y(X + c) - Y(X) = c * sum_k w^
+    # (checked through the oracle for both; here the kernel must follow the oracle on strongly one-sided tokens)
+    spec = _spec(8, 12, 512, 64, 0, out_dtype="fp32")
+    L = workloads.make_layer(spec)
+    L["X"] = (L["X"].float().abs() + 4.0).to(torch.bfloat16)
+    pk_o = orc.pack_weights_grouped(f32(L["W"]), L["s"].numpy(), 0)
+    pk = serq.g128_pack_weights(L["W"].to(DEV), L["s"].to(DEV), 0)
+    Xhat = workloads.permute_channels(L["X"], pk_o["perm"])
+    Xq_o, sc_o, z_o = orc.quantize_act_asym(f32(Xhat), pk_o["s_inv"], 8)
+    assert np.all(z_o == -128)                              # every token is one-sided: zero point at the end of the grid
+    Xq, sc, z = serq.quantize_act_asym(Xhat.to(DEV), pk.s_inv, 8)
+    for path in (serq.PATH_SKINNY, serq.PATH_MFMA):
+        Y = serq.g128_linear(Xq, sc, z, 8, pk.Wq, pk.gscale, pk.wsum, 12, 64, 512, out_dtype=torch.float32,
+                             flags_=serq.flags(path))
+        assert_y_close(Y, orc.linear_grouped(Xq_o, sc_o, z_o, pk_o["Wq"], pk_o["gscale"]), "one-sided tokens")
+
+
+def test_g128_config2_attention_projection():
+    _run(workloads.config2(), R_mode="random")
+
+
+@pytest.mark.parametrize("which,M", [("up", 1), ("up", 16), ("down", 1), ("down", 16), ("up", 256), ("down", 256),
+                                     ("up", 4096), ("down", 4096)])
+def test_g128_config3_mlp_pair(which, M):
+    _run(workloads.config3(which, M), R_mode="random")
+
+
+def test_g128_error_codes():
+    x = torch.zeros(64 * 128, dtype=torch.uint8, device=DEV)
+    f = torch.ones(64, dtype=torch.float32, device=DEV)
+    z = torch.zeros(64, dtype=torch.int32, device=DEV)
+    y = torch.empty((1, 64), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(serq.SerqError) as e:               # K not a multiple of 128
+        serq.g128_linear(x, f, z, 8, x, x, f, 1, 64, 192, Y=y)
+    assert e.value.code == -3
+    with pytest.raises(serq.SerqError) as e:
+        serq.g128_linear(x, f, z, 5, x, x, f, 1, 64, 128, Y=y)
+    assert e.value.code == -2
+    with pytest.raises(serq.SerqError) as e:               # the streaming kernel takes at most 32 tokens
+        serq.g128_linear(x, f, z, 8, x, x, f, 40, 64, 128, flags_=serq.flags(serq.PATH_SKINNY))
+    assert e.value.code == -3
+    with pytest.raises(serq.SerqError) as e:               # salient block past K
+        serq.g128_linear(x, f, z, 8, x, x, f, 1, 64, 128, Rp=x, r=64, s_begin=96, Y=y)
+    assert e.value.code == -3
+    assert serq.lib().serq_g128_scale_bytes(64, 256) == 64 * 2 * 2
+    assert serq.lib().serq_g128_scale_bytes(64, 192) == 0
+    assert serq.g128_linear(x, f, z, 8, x, x, f, 0, 64, 128).shape == (0, 64)
