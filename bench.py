@@ -345,7 +345,7 @@ def _time_launches(fn, n: int, reps: int = 3, graph: bool = False) -> float:
     return best
 
 
-def sweep():
+def sweep(only: str = ""):
     """Every benchmark configuration, one JSON line each: quantize_act and serq_linear timed separately
     (HIP events around back-to-back launches; decode-sized shapes rotate over copies of the weights that
     together exceed the Infinity Cache and are replayed from a HIP graph), with the roofline that bounds the row."""
@@ -354,6 +354,8 @@ def sweep():
     rows += [workloads.config3(w, M) for w in ("up", "down") for M in (1, 16, 256, 4096)]
     rows += [workloads.config4(M) for M in (1, 4, 32)]
     rows += [workloads.config5(layer, r) for layer in workloads.config5_layers() for r in (0, 32, 64, 128, 256)]
+    if only:
+        rows = [r_ for r_ in rows if any(tok in r_.name for tok in only.split(","))]
     cache = {}
     for spec in rows:
         key = (spec.cfg, spec.N, spec.K, spec.abits, spec.seed_index)
@@ -484,6 +486,54 @@ def sweep():
             row["mxfp4"] = {"r": rm, "quantize_act_us": round(mq_us, 2), "serq_mx_linear_us": round(ml_us, 2),
                             "tflops": round(ops / ml_us / 1e6, 1), "frac_of_fp4_peak": round(ops / ml_us / 1e6 / FP4_PEAK_TFLOPS, 4)}
             del mpk
+        if K % 128 == 0:
+            # the accuracy-table setting: group-128 weight scales + asymmetric activations (serq_g128_linear)
+            Lw = workloads.make_layer(spec, want=("s", "W"))
+            gpk = serq.g128_pack_weights(Lw["W"].to(dev), Lw["s"].to(dev), 0, perm_in=pk.perm)
+            del Lw
+            gcopy = int(np.ceil(640e6 / (gpk.Wq.numel() + gpk.gscale.numel()))) if small else 1
+            gW = [(gpk.Wq, gpk.gscale)] + [(gpk.Wq.clone(), gpk.gscale.clone()) for _ in range(gcopy - 1)]
+            za = torch.empty(M, dtype=torch.int32, device=dev)
+
+            def gq(i):
+                serq.quantize_act_asym(Xhat, gpk.s_inv, spec.abits, Xq=Xq, scale=scale, zero=za)
+
+            def glin(i):
+                wq, gs_ = gW[i % gcopy]
+                serq.g128_linear(Xq, scale, za, spec.abits, wq, gs_, gpk.wsum, M, N, K, Rp=Rps[0], r=r, Y=Y)
+
+            gq(0)
+            glin(0)
+            gq_us = _time_launches(gq, n, graph=small)
+            gl_us = _time_launches(glin, max(n, 2 * gcopy), graph=small)
+            g = {"quantize_act_asym_us": round(gq_us, 2), "serq_g128_linear_us": round(gl_us, 2)}
+            if small:
+                gb = decode_bytes(spec) + N * (K // 128) * 2 + 4 * N
+                g.update({"bytes": int(gb), "gbs": round(gb / gl_us / 1e3, 1), "frac_hbm_peak": round(gb / gl_us / 1e3 / HBM_PEAK_GBS, 4)})
+            else:
+                g.update({"tops": round(2.0 * M * N * K / gl_us / 1e6, 1),
+                          "frac_of_int8_peak": round(2.0 * M * N * K / gl_us / 1e6 / INT8_PEAK_TOPS, 4)})
+            row["g128_asym"] = g
+            del gW, gpk
+        if spec.cfg == 5 and r == 0 and spec.abits == 4 and ("_o_" in spec.name or "_down_" in spec.name):
+            # experiment: the same INT32 sums from one plain tiled kernel by two operand routes -- 4-bit codes
+            # widened for the int8 instruction, and FP6 (E2M3) codes on the block-scaled instruction
+            codes_w = serq.unpack_weights(pk.Wq, N, K)
+            codes_x = serq.unpack_act(Xq, 4, M, K)
+            W6 = serq.fp6_pack_weights(codes_w)
+            X6 = serq.fp6_pack_act(codes_x)
+            del codes_w, codes_x
+            acc = torch.empty((M, N), dtype=torch.int32, device=dev)
+            serq.proto_gemm_i32(Xq, pk.Wq, False, M, N, K, acc=acc)
+            spin_up(lambda: serq.proto_gemm_i32(X6, W6, True, M, N, K, acc=acc), 0.05)
+            i8_us = _time_launches(lambda i: serq.proto_gemm_i32(Xq, pk.Wq, False, M, N, K, acc=acc), n)
+            f6_us = _time_launches(lambda i: serq.proto_gemm_i32(X6, W6, True, M, N, K, acc=acc), n)
+            i8b_us = _time_launches(lambda i: serq.proto_gemm_i32(Xq, pk.Wq, False, M, N, K, acc=acc), n)
+            row["fp6_experiment"] = {"kernel": "proto_gemm_kernel (plain 128x128 tiles, INT32 out)",
+                                     "int8_route_us": round(min(i8_us, i8b_us), 2), "fp6_route_us": round(f6_us, 2),
+                                     "int8_route_tops": round(2.0 * M * N * K / min(i8_us, i8b_us) / 1e6, 1),
+                                     "fp6_route_tops": round(2.0 * M * N * K / f6_us / 1e6, 1)}
+            del W6, X6, acc
         print(json.dumps(row), flush=True)
         del Wqs, Rps, Rqs
 
@@ -508,6 +558,7 @@ def main():
     ap.add_argument("--no-mx", action="store_true", help="skip the MXFP4 leg of the default run")
     ap.add_argument("--mx", nargs="?", const="up", default=None, choices=["up", "down"],
                     help="time the MXFP4 variant of the layer on the headline shape (up, default) or its down projection instead")
+    ap.add_argument("--only", default="", help="with --sweep: comma-separated substrings of the workload names to time")
     ap.add_argument("--sweep", action="store_true", help="time every benchmark configuration (one JSON line per row) instead of the headline step")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -521,7 +572,7 @@ def main():
         calibrate_copy()
         return
     if a.sweep:
-        sweep()
+        sweep(a.only)
         return
     if a.mx:
         print(json.dumps(bench_mx(a.steps, a.warmup, a.mx)))

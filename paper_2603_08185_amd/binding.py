@@ -60,6 +60,11 @@ SIGNATURES = {
     "serq_g128_pack_weights": (_i, [_vp, _i, _vp, _vp, _i64, _i64, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp]),
     "serq_g128_unpack_scales": (_i, [_vp, _i64, _i64, _vp, _vp]),
     "serq_g128_linear": (_i, [_vp, _vp, _vp, _i, _vp, _vp, _vp, _i, _i, _vp, _i, _i64, _i64, _i64, _vp, _i, _i64, _i, _vp]),
+    "serq_fp6_weight_bytes": (_sz, [_i64, _i64]),
+    "serq_fp6_act_bytes": (_sz, [_i64, _i64]),
+    "serq_fp6_pack_weights": (_i, [_vp, _i64, _i64, _vp, _vp]),
+    "serq_fp6_pack_act": (_i, [_vp, _i64, _i64, _vp, _vp]),
+    "serq_proto_gemm_i32": (_i, [_vp, _vp, _i, _i64, _i64, _i64, _vp, _i64, _vp]),
     "serq_bench_mfma_peak": (_i, [_vp, _i, _i, _vp, _vp]),
     "serq_bench_mfma_fp4_peak": (_i, [_vp, _i, _i, _vp, _vp]),
     "serq_bench_read": (_i, [_vp, _sz, _i, _vp, _vp]),
@@ -475,14 +480,18 @@ def g128_unpack_scales(gscale: torch.Tensor, N: int, K: int) -> torch.Tensor:
     return out
 
 
-def quantize_act_asym(X: torch.Tensor, s_inv: Optional[torch.Tensor], abits: int):
+def quantize_act_asym(X: torch.Tensor, s_inv: Optional[torch.Tensor], abits: int, Xq: Optional[torch.Tensor] = None,
+                      scale: Optional[torch.Tensor] = None, zero: Optional[torch.Tensor] = None):
     """serq_quantize_act_asym: returns (Xq packed uint8 blob, scale fp32 [M], zero int32 [M])."""
     _rows(X, "X")
     M, K = X.shape
     L = lib()
-    Xq = torch.empty(max(L.serq_packed_act_bytes(M, K, abits), 16), dtype=torch.uint8, device=X.device)
-    scale = torch.empty(max(M, 1), dtype=torch.float32, device=X.device)[:M]
-    zero = torch.empty(max(M, 1), dtype=torch.int32, device=X.device)[:M]
+    if Xq is None:
+        Xq = torch.empty(max(L.serq_packed_act_bytes(M, K, abits), 16), dtype=torch.uint8, device=X.device)
+    if scale is None:
+        scale = torch.empty(max(M, 1), dtype=torch.float32, device=X.device)[:M]
+    if zero is None:
+        zero = torch.empty(max(M, 1), dtype=torch.int32, device=X.device)[:M]
     rc = L.serq_quantize_act_asym(_ptr(X), _DT[X.dtype], _ptr(s_inv), M, K, X.stride(0) if M > 0 else K, abits,
                                   _ptr(Xq), _ptr(scale), _ptr(zero), _stream())
     _check("serq_quantize_act_asym", rc)
@@ -500,3 +509,32 @@ def g128_linear(Xq: torch.Tensor, scale: torch.Tensor, zero: Optional[torch.Tens
                                 _ptr(Rp), _DT[r_dtype], M, N, K, _ptr(Y), _DT[Y.dtype], Y.stride(0), flags_, _stream())
     _check("serq_g128_linear", rc)
     return Y
+
+
+# ---- experiment: W4A4 integer sums on the FP6 form of the scaled matrix instruction -----------------------
+def fp6_pack_weights(codes: torch.Tensor) -> torch.Tensor:
+    """serq_fp6_pack_weights: canonical int8 codes [N,K] -> FP6 weight fragments."""
+    _dev(codes, "codes")
+    N, K = codes.shape
+    out = torch.empty(max(lib().serq_fp6_weight_bytes(N, K), 16), dtype=torch.uint8, device=codes.device)
+    _check("serq_fp6_pack_weights", lib().serq_fp6_pack_weights(_ptr(codes), N, K, _ptr(out), _stream()))
+    return out
+
+
+def fp6_pack_act(codes: torch.Tensor) -> torch.Tensor:
+    """serq_fp6_pack_act: canonical int8 codes [M,K] -> FP6 rows."""
+    _dev(codes, "codes")
+    M, K = codes.shape
+    out = torch.empty(max(lib().serq_fp6_act_bytes(M, K), 16), dtype=torch.uint8, device=codes.device)
+    _check("serq_fp6_pack_act", lib().serq_fp6_pack_act(_ptr(codes), M, K, _ptr(out), _stream()))
+    return out
+
+
+def proto_gemm_i32(X: torch.Tensor, W: torch.Tensor, fp6: bool, M: int, N: int, K: int,
+                   acc: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """serq_proto_gemm_i32: the INT32 sums from the plain tiled kernel, int8 route (fp6 = False) or FP6 route."""
+    if acc is None:
+        acc = torch.empty((M, N), dtype=torch.int32, device=X.device)
+    _check("serq_proto_gemm_i32", lib().serq_proto_gemm_i32(_ptr(X), _ptr(W), 1 if fp6 else 0, M, N, K, _ptr(acc),
+                                                            acc.stride(0) if M > 0 else N, _stream()))
+    return acc

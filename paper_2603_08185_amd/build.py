@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libserq.so")
 SOURCES = ["api.hip", "quantize_act.hip", "pack.hip", "skinny.hip", "gemm_mfma.hip", "gemm_mx.hip", "skinny_mx.hip",
-           "mx.hip", "peaks.hip", "noalloc.hip", "grouped.hip"]
+           "mx.hip", "peaks.hip", "noalloc.hip", "grouped.hip", "fp6.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
