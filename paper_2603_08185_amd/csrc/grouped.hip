@@ -339,15 +339,18 @@ __device__ __forceinline__ v16f mfma_lr16(const u4& r, const u4& x, v16f acc, bo
   return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, r), __builtin_bit_cast(v8h, x), acc, 0, 0, 0);
 }
 
-// ---- M <= 32: one workgroup of 4 waves per block of 32 output channels, weights streamed once ----------
-// Wave w takes the groups w, w+4, ... (two 1-KiB fragments each), folds each group's INT32 tile into its
-// fp32 tile, and the four waves are added through LDS in a fixed order (run-to-run identical).
+// ---- M <= 32: one workgroup of 8 waves per block of 32 output channels, weights streamed once ----------
+// Wave w takes the groups w, w+8, ... two at a time: the four 1-KiB weight fragments, the two groups' scales
+// and the token codes are all requested before the first is used.  Each group's INT32 tile is folded into
+// the wave's fp32 tile, the wave adds its share of the rank-r term, and the eight waves are added through
+// LDS in a fixed order (run-to-run identical).
 constexpr int kPitch = 36;
+constexpr int kSkinnyWaves = 8;
 template <int ABITS>
-__global__ __launch_bounds__(256) void serq_g128_skinny_kernel(const GParams p) {
+__global__ __launch_bounds__(64 * kSkinnyWaves) void serq_g128_skinny_kernel(const GParams p) {
   constexpr int SH = ABITS == 8 ? 4 : 8;
   constexpr float kInv = 1.0f / (float)(1 << SH);
-  __shared__ float red[4][2][32 * kPitch];
+  __shared__ float red[kSkinnyWaves][32 * kPitch];
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, m = l & 31, g = l >> 5;
   const int nb = blockIdx.x;
   const int KB = p.K >> 6, G = p.K >> 7;
@@ -361,72 +364,95 @@ __global__ __launch_bounds__(256) void serq_g128_skinny_kernel(const GParams p) 
   v16f accf;
 #pragma unroll
   for (int e = 0; e < 16; ++e) accf[e] = 0.0f;
-#pragma unroll 1
-  for (int grp = w; grp < G; grp += 4) {
-    const u4 w0 = __builtin_nontemporal_load(&wfr[(size_t)(2 * grp) * 64]);
-    const u4 w1 = __builtin_nontemporal_load(&wfr[(size_t)(2 * grp + 1) * 64]);
-    float gs[16];
-    load_gs16(gsb + (size_t)grp * 32, g, kInv, gs);
+  // the token operands of fragment fr: two int8x16 pieces (8-bit) or one packed piece (4-bit); zero without a token
+  auto load_x = [&](int fr, u4& x0, u4& x1) {
+    x0 = u4{0u, 0u, 0u, 0u};
+    x1 = x0;
+    if (mv) {
+      if constexpr (ABITS == 8) {
+        const uint8_t* xp = xrow + (size_t)fr * 64 + 32 * g;
+        x0 = *(const u4*)xp;
+        x1 = *(const u4*)(xp + 16);
+      } else {
+        x0 = *(const u4*)(xrow + (size_t)fr * 32 + 16 * g);
+      }
+    }
+  };
+  auto group_mfma = [&](const u4& wa, const u4& wb, const u4 (&x)[4], const float (&gs)[16]) {
     v16i acc;
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = 0;
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      v4i a0, a1, b0 = {0, 0, 0, 0}, b1 = {0, 0, 0, 0};
-      unpack_frag(u ? w1 : w0, a0, a1);
-      if (mv) {
-        if constexpr (ABITS == 8) {
-          const uint8_t* xp = xrow + (size_t)(2 * grp + u) * 64 + 32 * g;
-          b0 = *(const v4i*)xp;
-          b1 = *(const v4i*)(xp + 16);
-        } else {
-          unpack_frag(*(const u4*)(xrow + (size_t)(2 * grp + u) * 32 + 16 * g), b0, b1);
-        }
+      v4i a0, a1, b0, b1;
+      unpack_frag(u ? wb : wa, a0, a1);
+      if constexpr (ABITS == 8) {
+        b0 = as_v4i(x[2 * u]);
+        b1 = as_v4i(x[2 * u + 1]);
+      } else {
+        unpack_frag(x[2 * u], b0, b1);
       }
       acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, acc, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, acc, 0, 0, 0);
     }
 #pragma unroll
     for (int e = 0; e < 16; ++e) accf[e] = __builtin_fmaf(gs[e], (float)acc[e], accf[e]);
+  };
+#pragma unroll 1
+  for (int grp = w; grp < G; grp += 2 * kSkinnyWaves) {
+    const int grp2 = grp + kSkinnyWaves;
+    const bool two = grp2 < G;                            // uniform over the wave
+    const int gb = two ? grp2 : grp;                      // a wave without a second group repeats the first (unused)
+    const u4 w0 = __builtin_nontemporal_load(&wfr[(size_t)(2 * grp) * 64]);
+    const u4 w1 = __builtin_nontemporal_load(&wfr[(size_t)(2 * grp + 1) * 64]);
+    const u4 w2 = __builtin_nontemporal_load(&wfr[(size_t)(2 * gb) * 64]);
+    const u4 w3 = __builtin_nontemporal_load(&wfr[(size_t)(2 * gb + 1) * 64]);
+    u4 xa[4], xb[4];
+    load_x(2 * grp, xa[0], xa[1]);
+    load_x(2 * grp + 1, xa[2], xa[3]);
+    load_x(2 * gb, xb[0], xb[1]);
+    load_x(2 * gb + 1, xb[2], xb[3]);
+    float gsa[16], gsb2[16];
+    load_gs16(gsb + (size_t)grp * 32, g, kInv, gsa);
+    load_gs16(gsb + (size_t)gb * 32, g, kInv, gsb2);
+    group_mfma(w0, w1, xa, gsa);
+    if (two) group_mfma(w2, w3, xb, gsb2);
   }
-  // rank-r term on the re-centred codes
-  v16f accl;
-#pragma unroll
-  for (int e = 0; e < 16; ++e) accl[e] = 0.0f;
+  // rank-r term on the re-centred codes, added to the wave's tile
   const bool has_lr = p.r > 0 && p.Rp != nullptr;
   const bool bf = p.r_dtype == SERQ_BF16;
   if (has_lr) {
+    v16f accl;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) accl[e] = 0.0f;
     const int JB = p.r >> 4;
     const u4* rfr = p.Rp + (size_t)nb * JB * 64 + l;
-    for (int jb = w; jb < JB; jb += 4) {
+    for (int jb = w; jb < JB; jb += kSkinnyWaves) {
       const u4 rr = rfr[(size_t)jb * 64];
       const u4 xf = lr_operand<ABITS>(xrow, p.s_begin + 16 * jb + 8 * g, zm, mv, bf);
       accl = mfma_lr16(rr, xf, accl, bf);
     }
+#pragma unroll
+    for (int e = 0; e < 16; ++e) accf[e] += accl[e];
   }
   // combine: register 4i+e of lane (m,g) is channel 8i + 4g + e of token m
   if (mv) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      *(float4*)&red[w][0][m * kPitch + 8 * i + 4 * g] = make_float4(accf[4 * i], accf[4 * i + 1], accf[4 * i + 2], accf[4 * i + 3]);
-      *(float4*)&red[w][1][m * kPitch + 8 * i + 4 * g] = make_float4(accl[4 * i], accl[4 * i + 1], accl[4 * i + 2], accl[4 * i + 3]);
-    }
+    for (int i = 0; i < 4; ++i)
+      *(float4*)&red[w][m * kPitch + 8 * i + 4 * g] = make_float4(accf[4 * i], accf[4 * i + 1], accf[4 * i + 2], accf[4 * i + 3]);
   }
   __syncthreads();
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int id = tid + q * 256;
+  for (int q = 0; q < 1024 / (64 * kSkinnyWaves); ++q) {
+    const int id = tid + q * 64 * kSkinnyWaves;
     const int nl = id & 31, mt = id >> 5;
     if (mt >= p.M) continue;
-    float tot = 0.0f, lr = 0.0f;
+    float tot = 0.0f;
 #pragma unroll
-    for (int ww = 0; ww < 4; ++ww) {
-      tot += red[ww][0][mt * kPitch + nl];
-      lr += red[ww][1][mt * kPitch + nl];
-    }
+    for (int ww = 0; ww < kSkinnyWaves; ++ww) tot += red[ww][mt * kPitch + nl];
     const int n = nb * 32 + nl;
     const float zf = p.zero ? (float)p.zero[mt] : 0.0f;
-    const float y = p.scale[mt] * ((tot - zf * p.wsum[n]) + lr);
+    const float y = p.scale[mt] * (tot - zf * p.wsum[n]);
     const size_t o = (size_t)mt * p.ldy + n;
     if (p.y_dtype == SERQ_F32) ((float*)p.Y)[o] = y;
     else if (p.y_dtype == SERQ_BF16) ((uint16_t*)p.Y)[o] = f32_to_bf16_rne(y);
@@ -747,8 +773,8 @@ int serq_g128_linear(const void* Xq, const float* scale, const int32_t* zero, in
   const bool skinny = path == SERQ_PATH_SKINNY || (path == SERQ_PATH_AUTO && M <= 32);
   if (skinny) {
     dim3 grid((unsigned)(N / 32));
-    if (abits == 8) hipLaunchKernelGGL(serq_g128_skinny_kernel<8>, grid, dim3(256), 0, st, p);
-    else hipLaunchKernelGGL(serq_g128_skinny_kernel<4>, grid, dim3(256), 0, st, p);
+    if (abits == 8) hipLaunchKernelGGL(serq_g128_skinny_kernel<8>, grid, dim3(64 * kSkinnyWaves), 0, st, p);
+    else hipLaunchKernelGGL(serq_g128_skinny_kernel<4>, grid, dim3(64 * kSkinnyWaves), 0, st, p);
   } else {
     dim3 grid((unsigned)((N / 32 + 3) / 4), (unsigned)((M + 127) / 128));
     if (abits == 8) hipLaunchKernelGGL(serq_g128_tiled_kernel<8>, grid, dim3(256), 0, st, p);
