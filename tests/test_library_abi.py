@@ -159,6 +159,59 @@ def test_mx_and_fused_entry_points_validate_before_any_launch():
     assert lin(M=0) == 0
 
 
+def test_grouped_fp6_and_noalloc_entry_points_validate_before_any_launch():
+    L = serq.lib()
+    buf = (ctypes.c_char * 4096)()
+    a = (ctypes.cast(buf, ctypes.c_void_p).value + 15) & ~15
+    p = ctypes.c_void_p(a)
+    odd = ctypes.c_void_p(a + 4)
+    # group-128 / asymmetric variant
+    assert L.serq_g128_scale_bytes(11008, 4096) == 11008 * 32 * 2
+    assert L.serq_g128_scale_bytes(64, 192) == 0 and L.serq_g128_scale_bytes(48, 256) == 0
+    assert L.serq_quantize_act_asym(p, 7, None, 1, 64, 64, 4, p, p, p, None) == -2
+    assert L.serq_quantize_act_asym(p, 2, None, 1, 64, 64, 6, p, p, p, None) == -2
+    assert L.serq_quantize_act_asym(p, 2, None, 1, 100, 100, 4, p, p, p, None) == -3
+    assert L.serq_quantize_act_asym(p, 2, None, 1, 128, 64, 4, p, p, p, None) == -3      # ldx < K
+    assert L.serq_quantize_act_asym(p, 2, None, 1, 64, 68, 4, p, p, p, None) == -4
+    assert L.serq_quantize_act_asym(p, 2, None, 1, 64, 64, 4, p, p, None, None) == -1    # zero_out required
+    assert L.serq_quantize_act_asym(None, 2, None, 0, 64, 64, 4, None, None, None, None) == 0
+    def gpack(W=p, wdt=2, N=64, K=128, r=0, Wq=p, gs=p, ws_=p, perm=p, sinv=p, R=None, rdt=2, Rp=None):
+        return L.serq_g128_pack_weights(W, wdt, None, None, N, K, r, Wq, gs, ws_, perm, sinv, R, rdt, Rp, None)
+    assert gpack(W=None) == -1 and gpack(gs=None) == -1 and gpack(ws_=None) == -1
+    assert gpack(wdt=5) == -2
+    assert gpack(K=192) == -3 and gpack(N=48) == -3 and gpack(r=24) == -3 and gpack(r=256) == -3
+    assert gpack(r=16, Rp=p, rdt=0) == -2                # a packed R is 16-bit
+    assert gpack(Wq=odd) == -4
+    assert L.serq_g128_unpack_scales(None, 64, 128, p, None) == -1
+    assert L.serq_g128_unpack_scales(p, 64, 100, p, None) == -3
+    def glin(Xq=p, sc=p, z=p, ab=8, Wq=p, gs=p, ws_=p, s_begin=0, r=0, Rp=None, rdt=2, M=1, N=64, K=128, Y=p, ydt=2,
+             ldy=64, fl=0):
+        return L.serq_g128_linear(Xq, sc, z, ab, Wq, gs, ws_, s_begin, r, Rp, rdt, M, N, K, Y, ydt, ldy, fl, None)
+    assert glin(ab=5) == -2 and glin(ydt=7) == -2
+    assert glin(K=192) == -3 and glin(N=48) == -3 and glin(ldy=32) == -3
+    assert glin(r=24, Rp=p) == -3 and glin(s_begin=16, r=16, Rp=p) == -3 and glin(s_begin=96, r=64, Rp=p) == -3
+    assert glin(r=16, Rp=p, rdt=0) == -2
+    assert glin(gs=None) == -1 and glin(ws_=None) == -1 and glin(sc=None) == -1
+    assert glin(ldy=68) == -4 and glin(Y=odd) == -4 and glin(z=ctypes.c_void_p(a + 2)) == -4
+    assert glin(M=40, fl=1) == -3 and glin(fl=9) == -7
+    assert glin(M=0) == 0
+    # FP6 experiment
+    assert L.serq_fp6_weight_bytes(4096, 4096) == 4096 * 4096 * 3 // 4
+    assert L.serq_fp6_weight_bytes(4096, 192) == 0 and L.serq_fp6_act_bytes(5, 256) == 5 * 192
+    assert L.serq_fp6_pack_weights(None, 64, 128, p, None) == -1
+    assert L.serq_fp6_pack_weights(p, 64, 192, p, None) == -3
+    assert L.serq_fp6_pack_act(p, 1, 192, p, None) == -3
+    assert L.serq_fp6_pack_act(None, 0, 128, None, None) == 0
+    assert L.serq_proto_gemm_i32(p, p, 1, 1, 64, 192, p, 64, None) == -3
+    assert L.serq_proto_gemm_i32(p, p, 1, 1, 64, 128, p, 32, None) == -3          # ldacc < N
+    assert L.serq_proto_gemm_i32(p, None, 0, 1, 64, 128, p, 64, None) == -1
+    assert L.serq_proto_gemm_i32(p, p, 0, 1, 64, 128, odd, 64, None) == -4
+    assert L.serq_proto_gemm_i32(None, None, 0, 0, 64, 128, None, 64, None) == 0
+    # the allocation-free entry point refuses layers wider than its built-in scratch before it touches the device
+    assert L.serq_linear_noalloc(p, p, 4, p, p, 0, 0, None, 2, 1, 32768 + 32, 64, p, 2, 32768 + 32, 0, None) == -8
+    assert b"scratch" in L.serq_strerror(-8)
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(serq, "_lib", None)
     monkeypatch.setattr(serq, "LIB_PATH", "/nonexistent/libserq.so")
