@@ -212,10 +212,25 @@ def decode_bytes(spec) -> float:
     return N * K / 2 + 2.0 * r * N + 4 * N + M * K * spec.abits / 8 + 4 * M + M * N * out_b
 
 
-def bench_decode(L, pk, reps: int = 5):
-    """M = 1 on the same layer; weights + R rotated over > 512 MB of distinct copies."""
+def read_stick(nbytes: int) -> float:
+    """GB/s of a launch that only reads `nbytes` (rotating over > 640 MB of distinct buffers, replayed from a graph):
+    what a decode-sized call of that many bytes could reach at best on this part."""
     dev = "cuda:0"
-    spec = workloads.config3("up", 1)
+    nbytes = nbytes // 16 * 16
+    ncopy = int(np.ceil(640e6 / nbytes))
+    big = torch.empty(ncopy * nbytes, dtype=torch.uint8, device=dev).fill_(1)
+    views = [big[i * nbytes:(i + 1) * nbytes] for i in range(ncopy)]
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    rd = lambda i: serq.bench_read(views[i % ncopy], nbytes, 2048, sink)
+    spin_up(lambda: rd(0), 0.05)
+    us = _time_launches(rd, max(4 * ncopy, 20), graph=True)
+    return nbytes / us / 1e3
+
+
+def bench_decode(L, pk, reps: int = 5, spec=None):
+    """M = 1 on the given layer (default: the benchmark's own); weights + R rotated over > 640 MB of distinct copies."""
+    dev = "cuda:0"
+    spec = spec or workloads.config3("up", 1)
     M, N, K = 1, spec.N, spec.K
     X1 = workloads.make_layer(spec, want=("X",))["X"]
     Xhat = workloads.permute_channels(X1, pk.perm.cpu().numpy()).to(dev)
@@ -607,7 +622,21 @@ def main():
     if not a.no_decode:
         d = bench_decode(L, pk)
         d["frac_of_measured_read_peak"] = d["gbs_hbm"] / mp["read_gbs_decode_size"]
+        d["read_only_launch_gbs"] = mp["read_gbs_decode_size"]
+        # can a call of this size reach 70 % of 8 TB/s at all?  A launch that only reads the same bytes says.
+        d["target_0.70_reachable"] = bool(mp["read_gbs_decode_size"] >= 0.70 * HBM_PEAK_GBS)
         out["decode"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in d.items()}
+        # the wide decode layer of configs[3] (W4A4, K=8192, N=28672: 125 MB per call), M = 1
+        spec4 = workloads.config4(1)
+        L4 = workloads.make_layer(spec4, want=("s", "W", "R"))
+        pk4 = serq.pack_weights(L4["W"].to("cuda:0"), L4["s"].to("cuda:0"), 0, want_R=False, want_Rp=False)
+        d4 = bench_decode(L4, pk4, reps=3, spec=spec4)
+        stick4 = read_stick(int(decode_bytes(spec4)))
+        d4["read_only_launch_gbs"] = stick4
+        d4["frac_of_measured_read_peak"] = d4["gbs_hbm"] / stick4
+        d4["target_0.70_reachable"] = bool(stick4 >= 0.70 * HBM_PEAK_GBS)
+        out["decode_cfg4"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in d4.items()}
+        del L4, pk4
     if not a.no_mx:
         # the MXFP4 variant of the same layer (its own line with `--mx`): step, layer kernel, quantiser
         mx = bench_mx(min(a.steps, 300), min(a.warmup, 30))

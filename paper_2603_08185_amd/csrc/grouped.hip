@@ -17,6 +17,7 @@
 // weight-streaming kernel for M <= 32 and an LDS-tiled kernel above, and their C entry points.
 // Weight codes use the fragment layout of the per-channel path (serq_unpack_weights reads them back);
 // group scales: [N/32][K/128][32 channels] fp16.
+#include "gemm_tile.h"
 #include "serq_device.h"
 
 namespace serq {
@@ -307,16 +308,20 @@ __device__ __forceinline__ void store_y(const GParams& p, int m, int n, const fl
   else *(u2*)((uint16_t*)p.Y + o) = u2{f32x2_to_f16x2(y[0], y[1]), f32x2_to_f16x2(y[2], y[3])};
 }
 
-// the 16 group scales a lane needs for one 32-channel block: channels 8i + 4g + 0..3, i = 0..3, times 2^-SH
-__device__ __forceinline__ void load_gs16(const uint16_t* blk, int g, float kinv, float gs[16]) {
+// the 16 group scales a lane needs for one 32-channel block: channels 8i + 4g + 0..3, i = 0..3, as stored
+// (fp16: the fold below widens them inside a mixed-precision fused multiply-add)
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+struct GS16 { h4 v[4]; };
+__device__ __forceinline__ GS16 load_gs16(const uint16_t* blk, int g) {
+  GS16 r;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint2 h = *(const uint2*)(blk + 8 * i + 4 * g);
-    gs[4 * i + 0] = f16bits_to_f32((uint16_t)(h.x & 0xffffu)) * kinv;
-    gs[4 * i + 1] = f16bits_to_f32((uint16_t)(h.x >> 16)) * kinv;
-    gs[4 * i + 2] = f16bits_to_f32((uint16_t)(h.y & 0xffffu)) * kinv;
-    gs[4 * i + 3] = f16bits_to_f32((uint16_t)(h.y >> 16)) * kinv;
-  }
+  for (int i = 0; i < 4; ++i) r.v[i] = *(const h4*)(blk + 8 * i + 4 * g);
+  return r;
+}
+// accf += gscale * acc for one 32 x 32 tile (register e: channel 8*(e/4) + 4g + e%4)
+__device__ __forceinline__ void fold_tile(const GS16& gs, const v16i& acc, v16f& accf) {
+#pragma unroll
+  for (int e = 0; e < 16; ++e) accf[e] = __builtin_fmaf((float)gs.v[e >> 2][e & 3], (float)acc[e], accf[e]);
 }
 
 // 8 re-centred codes (code - zero) of one lane as exact 16-bit floats; all zero for a lane without a token
@@ -378,7 +383,7 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void serq_g128_skinny_kernel(con
       }
     }
   };
-  auto group_mfma = [&](const u4& wa, const u4& wb, const u4 (&x)[4], const float (&gs)[16]) {
+  auto group_mfma = [&](const u4& wa, const u4& wb, const u4 (&x)[4], const GS16& gs) {
     v16i acc;
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = 0;
@@ -395,8 +400,7 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void serq_g128_skinny_kernel(con
       acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, acc, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, acc, 0, 0, 0);
     }
-#pragma unroll
-    for (int e = 0; e < 16; ++e) accf[e] = __builtin_fmaf(gs[e], (float)acc[e], accf[e]);
+    fold_tile(gs, acc, accf);
   };
 #pragma unroll 1
   for (int grp = w; grp < G; grp += 2 * kSkinnyWaves) {
@@ -412,9 +416,8 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void serq_g128_skinny_kernel(con
     load_x(2 * grp + 1, xa[2], xa[3]);
     load_x(2 * gb, xb[0], xb[1]);
     load_x(2 * gb + 1, xb[2], xb[3]);
-    float gsa[16], gsb2[16];
-    load_gs16(gsb + (size_t)grp * 32, g, kInv, gsa);
-    load_gs16(gsb + (size_t)gb * 32, g, kInv, gsb2);
+    const GS16 gsa = load_gs16(gsb + (size_t)grp * 32, g);
+    const GS16 gsb2 = load_gs16(gsb + (size_t)gb * 32, g);
     group_mfma(w0, w1, xa, gsa);
     if (two) group_mfma(w2, w3, xb, gsb2);
   }
@@ -433,7 +436,10 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void serq_g128_skinny_kernel(con
       accl = mfma_lr16(rr, xf, accl, bf);
     }
 #pragma unroll
-    for (int e = 0; e < 16; ++e) accf[e] += accl[e];
+    for (int e = 0; e < 16; ++e) accf[e] = __builtin_fmaf(accf[e], kInv, accl[e]);   // 2^-SH: exact
+  } else {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) accf[e] *= kInv;
   }
   // combine: register 4i+e of lane (m,g) is channel 8i + 4g + e of token m
   if (mv) {
@@ -486,9 +492,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, lm = l & 31, g = l >> 5;
   const int wn = w & 1, wm = w >> 1;
   const int NB = p.N >> 5, KB = p.K >> 6, G = p.K >> 7;
-  const int nb0 = blockIdx.x * 4;
+  // workgroup id -> tile: one contiguous range of tiles per XCD, in bands of 8 token tiles, so that the
+  // tiles in flight on one XCD share their weight and token panels in its L2
+  int tile_m, tile_n;
+  map_block(blockIdx.x, (p.M + 127) >> 7, (NB + 3) >> 2, 8, tile_m, tile_n);
+  const int nb0 = tile_n * 4;
   const int nbt = NB - nb0 < 4 ? NB - nb0 : 4;
-  const int m0 = blockIdx.y * 128;
+  const int m0 = tile_m * 128;
   const int mrows = p.M - m0 < 128 ? p.M - m0 : 128;
   const size_t rowbytes = (size_t)p.K * ABITS / 8;
 
@@ -545,6 +555,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   v16i acc[2][2];
   v16f accf[2][2];
+  const v16i kZero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -559,9 +570,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   for (int gi = 0; gi < G; ++gi) {
     const bool more = gi + 1 < G;
     if (more) fetch(gi + 1);
-    float gs[2][16];
+    GS16 gs[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) load_gs16(p.gsc + ((size_t)bi[i] * G + gi) * 32, g, kInv, gs[i]);
+    for (int i = 0; i < 2; ++i) gs[i] = load_gs16(p.gsc + ((size_t)bi[i] * G + gi) * 32, g);
     const uint8_t* s = lds + (gi & 1) * T::STAGE;
 #pragma unroll
     for (int f = 0; f < 2; ++f) {
@@ -582,7 +593,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[i], b0[j], acc[i][j], 0, 0, 0);
+          // the first product of a group starts from zero (a constant operand, no registers to clear)
+          if (f == 0) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[i], b0[j], kZero16, 0, 0, 0);
+          else acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[i], b0[j], acc[i][j], 0, 0, 0);
           acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[i], b1[j], acc[i][j], 0, 0, 0);
         }
     }
@@ -590,12 +603,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          accf[i][j][e] = __builtin_fmaf(gs[i][e], (float)acc[i][j][e], accf[i][j][e]);
-          acc[i][j][e] = 0;
-        }
+      for (int j = 0; j < 2; ++j) fold_tile(gs[i], acc[i][j], accf[i][j]);
     if (more) park((gi + 1) & 1);
     __syncthreads();
   }
@@ -625,7 +633,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) accf[i][j][e] = __builtin_fmaf(-(float)zm[j], ws[e], accf[i][j][e]);
+      for (int e = 0; e < 16; ++e) accf[i][j][e] = __builtin_fmaf(accf[i][j][e], kInv, -(float)zm[j] * ws[e]);   // 2^-SH: exact
   }
   if (has_lr) {
     const int JB = p.r >> 4;
@@ -776,7 +784,9 @@ int serq_g128_linear(const void* Xq, const float* scale, const int32_t* zero, in
     if (abits == 8) hipLaunchKernelGGL(serq_g128_skinny_kernel<8>, grid, dim3(64 * kSkinnyWaves), 0, st, p);
     else hipLaunchKernelGGL(serq_g128_skinny_kernel<4>, grid, dim3(64 * kSkinnyWaves), 0, st, p);
   } else {
-    dim3 grid((unsigned)((N / 32 + 3) / 4), (unsigned)((M + 127) / 128));
+    const long long tiles = (long long)((N / 32 + 3) / 4) * ((M + 127) / 128);
+    if (tiles > 0x7fffffffLL) return SERQ_ESHAPE;
+    dim3 grid((unsigned)tiles);
     if (abits == 8) hipLaunchKernelGGL(serq_g128_tiled_kernel<8>, grid, dim3(256), 0, st, p);
     else hipLaunchKernelGGL(serq_g128_tiled_kernel<4>, grid, dim3(256), 0, st, p);
   }
