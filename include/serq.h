@@ -62,7 +62,8 @@ extern "C" {
 #define SERQ_PATH_AUTO   0     /* by M: skinny for M <= 32, tiled MFMA above    */
 #define SERQ_PATH_SKINNY 1     /* weight-streaming split-K kernel (M <= 32)     */
 #define SERQ_PATH_MFMA   2     /* LDS-tiled int8-MFMA kernel                    */
-/* bits 8..15 of `flags`: split-K factor override for the skinny path (0 = auto) */
+/* bits 8..15 of `flags`: number of K slices (0 = the library's choice; 1 = none; n > 1 = exactly n, which
+ * needs the workspace) -- of the skinny path's channel blocks, or of the MFMA path's output tiles */
 #define SERQ_FLAG_SPLITK(n) (((n) & 0xff) << 8)
 /* bits 16..19 of `flags`: MFMA path: token-tile group height of the block order (0 = auto);
  * skinny path: waves per workgroup / 4 (1 or 2; anything else = auto) */
@@ -80,9 +81,11 @@ size_t serq_packed_lowrank_bytes(int64_t N, int r);                /* Rp (16-bit
 size_t serq_packed_lowrank_q4_bytes(int64_t N, int r);             /* Rq (4-bit codes + rscale) */
 size_t serq_workspace_bytes(int64_t M, int64_t N, int64_t K, int r, int abits);
 
-/* Zero a workspace before its first use.  serq_linear / serq_gemm_i32 leave it
- * zeroed again when they finish, so one call after allocation is enough.  Two
- * calls that share a workspace must not overlap in time. */
+/* Zero a workspace before its first use.  serq_linear / serq_gemm_i32 leave the part
+ * that must be zero (the decode path's meeting words, at its start) zeroed again when
+ * they finish, so one call after allocation is enough; the rest (where the tiled path
+ * parks the INT32 tiles of its K slices for layers with few tokens and a long K) is
+ * scratch.  Two calls that share a workspace must not overlap in time. */
 int serq_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 
 /*
@@ -190,7 +193,8 @@ int serq_swiglu_quantize_act(const void* G, const void* U, int x_dtype, const fl
  * (s_begin + 64*ceil(r/64) <= K; the codes past r meet zero weights).
  *   Y [M,N] in y_dtype (fp32/fp16/bf16), row stride ldy elements (multiple of 8).
  *   workspace: serq_workspace_bytes(...) bytes prepared by serq_workspace_init
- * (the decode path uses it when it cuts K into slices; pass NULL/0 to forbid that).
+ * (both paths use it when they cut K into slices; pass NULL/0 to forbid that).  Sliced or
+ * not, the INT32 sums are the same integers, so Y does not depend on it.
  *   flags: SERQ_PATH_* | SERQ_FLAG_*.
  */
 int serq_linear(const void* Xq, const float* scale, int abits,

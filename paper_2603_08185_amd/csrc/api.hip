@@ -70,9 +70,11 @@ size_t serq_packed_lowrank_q4_bytes(int64_t N, int r) {
 }
 
 size_t serq_workspace_bytes(int64_t M, int64_t N, int64_t K, int r, int abits) {
-  (void)M; (void)r; (void)abits;
-  if (check_nk(N, K) != SERQ_OK || M < 0) return 0;
-  return skinny_workspace_bytes((int)N);             // where the slices of a channel block meet (decode path)
+  (void)r;
+  if (check_nk(N, K) != SERQ_OK || M < 0 || M > (1 << 30) || (abits != 4 && abits != 8)) return 0;
+  // where the K slices of a channel block meet (decode path), then the parked INT32 tiles of the tiled
+  // path's K slices (only layers with few tokens and a long K are sliced there)
+  return skinny_workspace_bytes((int)N) + (M > 32 ? mfma_split_workspace_bytes((int)M, (int)N, (int)K, abits, 0) : 0);
 }
 
 int serq_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {

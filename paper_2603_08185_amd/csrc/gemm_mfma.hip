@@ -88,6 +88,14 @@ struct MfmaParams {
   int32_t* acc_out; int64_t ldacc;
   int tiles_m, tiles_n, groupm;
   int wide, nwide;        // column tiles 0..nwide-1 have `wide` blocks of 32 channels, the rest wide-1
+  // K slicing for layers whose tiles alone leave most compute units idle (two launches of this kernel):
+  //   pass 1 (kslices > 1, reduce = 0): grid (tiles, kslices); workgroup (tile, s) multiplies slice s of K and
+  //     parks its raw INT32 tile in `part`, in register order (every store a full 1-KiB wave row);
+  //   pass 2 (reduce = 1): grid (tiles); no main tiles -- the accumulators start as the sum of the parked
+  //     tiles (integer addition: the same bits as an unsliced run), then the usual epilogue.
+  int kslices, reduce;
+  int4* part;             // [kslices][tiles][8 waves][hm8][64 lanes]
+  int hm8;                // 8 x the largest number of channel blocks a wave owns (wide rounded up to even, / 2)
 };
 
 // ---- operand fragments ---------------------------------------------------------
@@ -131,14 +139,25 @@ void serq_mfma_kernel(const MfmaParams p) {
   const int half = (nbt + 1) >> 1;
   const int blk0 = __builtin_amdgcn_readfirstlane(wn ? half : 0);              // this wave's first block in the tile
   const int nbw = __builtin_amdgcn_readfirstlane(wn ? nbt - half : half);      // and how many it owns (0..4)
-  const int KB = p.K >> 6;
+  const int KBg = p.K >> 6;                          // fragments per channel block in memory
+  // the main tiles [ta, tb) this workgroup multiplies: all of them, one K slice (pass 1), or none (pass 2)
+  const bool part_out = p.kslices > 1 && !p.reduce;
+  int ta = 0, tb = (KBg + CH - 1) / CH;
+  if (part_out) {
+    const int per = tb / p.kslices, rem = tb % p.kslices, sl = blockIdx.y;
+    ta = sl * per + (sl < rem ? sl : rem);
+    tb = ta + per + (sl < rem ? 1 : 0);
+  } else if (p.reduce) {
+    tb = 0;
+  }
+  const int KB = (tb * CH < KBg ? tb * CH : KBg) - ta * CH;   // this workgroup's fragments
   const uint32_t rowbytes = (uint32_t)p.K * ABITS / 8;
   const int mrows = p.M - m0 < BM ? p.M - m0 : BM;   // valid token rows of this tile
 
   const int KTF = KB / CH;                           // full main tiles
   const int KTAIL = KB - KTF * CH;                   // fragments of a last, partial main tile
   const int KT = KTF + (KTAIL ? 1 : 0);
-  const int JB = (p.acc_out == nullptr) ? (p.r >> 4) : 0;
+  const int JB = (p.acc_out == nullptr && !part_out) ? (p.r >> 4) : 0;
   const int LT = (JB + 3) >> 2;                      // low-rank tiles of 64 salient channels (16-bit R: up to 4 x 16)
   constexpr bool lr_int = LRT == SERQ_I4;            // one weight-like fragment per tile and block
   const int TT = KT + LT;
@@ -161,7 +180,7 @@ void serq_mfma_kernel(const MfmaParams p) {
     const int f = i * kWaves + wu;
     int nbl = f / CH;
     nbl = nbl < nbt ? nbl : nbt - 1;                 // blocks past the tile: duplicates, never read
-    wv[i] = (uint32_t)((nbl * KB + (f % CH)) * 1024 + l * 16);
+    wv[i] = (uint32_t)((nbl * KBg + (f % CH)) * 1024 + l * 16);
   }
   // tokens: LDS piece pc = 512*i + tid -> row pc/8, slot pc%8 holds global piece slot ^ swizzle(row)
   uint32_t xv[T::NLX];
@@ -173,14 +192,15 @@ void serq_mfma_kernel(const MfmaParams p) {
     row = row < mrows ? row : mrows - 1;             // rows past M: duplicates, never stored
     xv[i] = (uint32_t)row * rowbytes + 16u * c;
   }
-  const uint8_t* wbase = (const uint8_t*)p.Wq + (size_t)nb0 * KB * 1024;
+  const uint8_t* wbase = (const uint8_t*)p.Wq + ((size_t)nb0 * KBg + (size_t)ta * CH) * 1024;
   const uint8_t* xbase = p.Xq + (size_t)m0 * rowbytes;
+  const uint8_t* xmain = xbase + (size_t)ta * 128;     // token codes of this workgroup's first main tile
 
   // k-th direct load of main tile t into stage st (k < NL)
   auto issue_main_one = [&](int t, int st, int k) {
     const uint32_t sb = lds0 + (uint32_t)st * STAGE + (uint32_t)wu * 1024;
     if (k < T::NLW) dma16(wbase + (size_t)t * CH * 1024, wv[k], sb + kWaves * 1024 * k);
-    else dma16(xbase + (size_t)t * 128, xv[k - T::NLW], sb + T::W_BYTES + kWaves * 1024 * (k - T::NLW));
+    else dma16(xmain + (size_t)t * 128, xv[k - T::NLW], sb + T::W_BYTES + kWaves * 1024 * (k - T::NLW));
   };
   // a main tile whose fragments / pieces may run past K: clamp them into the tile's first fragment
   auto issue_main_tail = [&](int t, int st) {
@@ -192,7 +212,7 @@ void serq_mfma_kernel(const MfmaParams p) {
       int nbl = f / CH, ch = f % CH;
       nbl = nbl < nbt ? nbl : nbt - 1;
       ch = ch < nf ? ch : 0;
-      dma16(wbase + (size_t)t * CH * 1024, (uint32_t)((nbl * KB + ch) * 1024 + l * 16), sb + kWaves * 1024 * i);
+      dma16(wbase + (size_t)t * CH * 1024, (uint32_t)((nbl * KBg + ch) * 1024 + l * 16), sb + kWaves * 1024 * i);
     }
     const int npc = nf * (ABITS == 8 ? 4 : 2);       // valid 16-byte pieces of a token row
 #pragma unroll
@@ -202,7 +222,7 @@ void serq_mfma_kernel(const MfmaParams p) {
       int c = (pc & 7) ^ ((row >> 1) & 7);
       c = c < npc ? c : 0;
       row = row < mrows ? row : mrows - 1;
-      dma16(xbase + (size_t)t * 128, (uint32_t)row * rowbytes + 16u * c, sb + T::W_BYTES + kWaves * 1024 * i);
+      dma16(xmain + (size_t)t * 128, (uint32_t)row * rowbytes + 16u * c, sb + T::W_BYTES + kWaves * 1024 * i);
     }
   };
   // low-rank tile lt (4 x 16 salient channels) into stage st
@@ -434,6 +454,39 @@ void serq_mfma_kernel(const MfmaParams p) {
     // register e of lane l in tile (i,j): channel n0 + 32*(blk0+i) + 8*(e/4) + 4*g + e%4,
     //                                     token   m0 + 64*wm + 32*j + lm.
     const int mbase = m0 + 64 * wm + lm;
+
+    if (p.kslices > 1) {
+      // register (i, j, q4) of lane l <-> int4 ((w * hm8 + (2*i + j) * 4 + q4) * 64 + l) of the tile's slot
+      const size_t slot = (size_t)kWaves * p.hm8 * 64;
+      int4* mine = p.part + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * slot + (size_t)w * p.hm8 * 64 + l;
+      if (part_out) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (i < NBW)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+              for (int q4 = 0; q4 < 4; ++q4)
+                mine[((2 * i + j) * 4 + q4) * 64] = make_int4(acc[i][j][4 * q4], acc[i][j][4 * q4 + 1], acc[i][j][4 * q4 + 2],
+                                                             acc[i][j][4 * q4 + 3]);
+        return;
+      }
+      // pass 2: the accumulators are the sum of the slices' tiles (blockIdx.y is 0 here)
+      for (int sl = 0; sl < p.kslices; ++sl) {
+        const int4* src = mine + (size_t)sl * gridDim.x * slot;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (i < NBW)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+              for (int q4 = 0; q4 < 4; ++q4) {
+                const int4 v = src[((2 * i + j) * 4 + q4) * 64];
+                acc[i][j][4 * q4] += v.x; acc[i][j][4 * q4 + 1] += v.y;
+                acc[i][j][4 * q4 + 2] += v.z; acc[i][j][4 * q4 + 3] += v.w;
+              }
+      }
+    }
 
     if (p.acc_out) {
 #pragma unroll
@@ -667,6 +720,69 @@ void serq_mfma_kernel(const MfmaParams p) {
 
 }  // namespace
 
+// ---- K slicing: when and how (host side) ---------------------------------------------------------
+// A layer with few tokens gives few tiles: one token tile x the column tiles.  Narrow column tiles fill more
+// compute units but every one of them walks all of K re-reading its whole token panel from LDS, so the step
+// gets no cheaper; cutting K into S slices instead multiplies the workgroups by S at the price of parking
+// S INT32 tiles per output tile and a second launch that adds them up.  The plan below prices both with a
+// small model fitted to measurements (cycles of one 64-channel step of a tile of b channel blocks; 5 TB/s for
+// the parked tiles, written and read once; 3 us for the second launch) and slices only when that wins.
+struct SplitPlan { int C, wide, nwide, S; };
+
+inline float step_cycles(int b, int abits) {
+  const float mfma = 128.0f * b, lds = abits == 8 ? 40.0f * b + 384.0f : 40.0f * b + 192.0f;
+  return 1.3f * (mfma > lds ? mfma : lds);
+}
+
+inline SplitPlan plan_split(int M, int N, int K, int abits, int ncu, int forced) {
+  const int NB = N / 32, tiles_m = (M + BM - 1) / BM;
+  const int CHh = abits == 8 ? 2 : 4;
+  const int KT = (K / 64 + CHh - 1) / CHh;             // main tiles
+  SplitPlan best;
+  plan_columns(tiles_m, NB, ncu, best.C, best.wide, best.nwide);
+  best.S = 1;
+  if (forced == 1) return best;
+  if (forced > 1) {
+    best.S = forced < KT ? forced : KT;
+    return best;
+  }
+  if ((long long)tiles_m * best.C * 4 >= 3LL * ncu || M > 512 || KT < 8) return best;   // the tiles fill the part well enough
+  const float steps = (float)(K / 64);
+  auto cost = [&](int C, int wide, int S) {
+    const long long wg = (long long)tiles_m * C * S;
+    const float rounds = (float)((wg + ncu - 1) / ncu);
+    float us = rounds * (steps / S) * step_cycles(wide, abits) / 2000.0f;
+    if (S > 1) us += 2.0f * ((float)S * M * N * 4.0f) / 5.0e6f + 3.0f;
+    return us;
+  };
+  float bc = cost(best.C, best.wide, 1);
+  const int cand[] = {2, 3, 4, 6, 8, 12, 16};
+  for (int wide = 1; wide <= 8; ++wide) {
+    const int C = (NB + wide - 1) / wide;
+    const int w2 = (NB + C - 1) / C;                    // the width this many tiles really have
+    for (int S : cand) {
+      if (S * 2 > KT || (long long)tiles_m * C * S > 2LL * ncu) continue;
+      const float c = cost(C, w2, S);
+      if (c < bc * 0.9f) {                              // only for a clear win: the model is rough
+        bc = c;
+        best.C = C; best.wide = w2; best.nwide = NB - C * (w2 - 1); best.S = S;
+      }
+    }
+  }
+  return best;
+}
+
+inline int wave_blocks8(int wide) { const int h = (wide + 1) / 2; return 8 * (h < 1 ? 1 : h); }
+
+// bytes of workspace the sliced path needs for this call (0: not sliced); `forced` as LinearArgs::splitk
+size_t mfma_split_workspace_bytes(int M, int N, int K, int abits, int forced) {
+  if (M <= 0) return 0;
+  const SplitPlan pl = plan_split(M, N, K, abits, device_cu_count(), forced);
+  if (pl.S <= 1) return 0;
+  const size_t tiles = (size_t)((M + BM - 1) / BM) * pl.C;
+  return (size_t)pl.S * tiles * kWaves * wave_blocks8(pl.wide) * 64 * sizeof(int4);
+}
+
 int launch_mfma(const LinearArgs& a, hipStream_t st) {
   const int ncu = device_cu_count();
   MfmaParams p;
@@ -677,7 +793,18 @@ int launch_mfma(const LinearArgs& a, hipStream_t st) {
   p.Y = a.Y; p.y_dtype = a.y_dtype; p.ldy = a.ldy;
   p.acc_out = a.acc_out; p.ldacc = a.ldacc;
   p.tiles_m = (a.M + BM - 1) / BM;
-  plan_columns(p.tiles_m, a.N / 32, ncu, p.tiles_n, p.wide, p.nwide);
+  // K slices need their part of the workspace (it lies behind the decode path's words); without it, none
+  const size_t ws_skip = skinny_workspace_bytes(a.N);
+  const size_t ws_have = (a.workspace && a.workspace_bytes > ws_skip) ? a.workspace_bytes - ws_skip : 0;
+  SplitPlan pl = plan_split(a.M, a.N, a.K, a.abits, ncu, a.coltiles > 0 && a.splitk == 0 ? 1 : a.splitk);
+  if (pl.S > 1) {
+    const size_t need = (size_t)pl.S * p.tiles_m * pl.C * kWaves * wave_blocks8(pl.wide) * 64 * sizeof(int4);
+    if (need > ws_have) {
+      if (a.splitk > 1) return SERQ_EWORKSPACE;         // an explicit request cannot be honoured
+      pl = plan_split(a.M, a.N, a.K, a.abits, ncu, 1);
+    }
+  }
+  p.tiles_n = pl.C; p.wide = pl.wide; p.nwide = pl.nwide;
   if (a.coltiles > 0) {                               // caller's override of the column tiling
     const int NB = a.N / 32;
     int C = a.coltiles < (NB + 7) / 8 ? (NB + 7) / 8 : (a.coltiles > NB ? NB : a.coltiles);
@@ -686,21 +813,35 @@ int launch_mfma(const LinearArgs& a, hipStream_t st) {
     p.nwide = NB - C * (p.wide - 1);
   }
   p.groupm = a.groupm > 0 ? a.groupm : 4;
+  p.kslices = pl.S; p.reduce = 0;
+  p.hm8 = wave_blocks8(p.wide);
+  p.part = pl.S > 1 ? (int4*)((char*)a.workspace + ws_skip) : nullptr;
   const long long tiles = (long long)p.tiles_m * p.tiles_n;
   if (tiles > 0x7fffffffLL) return SERQ_ESHAPE;
-  dim3 grid((unsigned)tiles), block(kThreads);
+  if (pl.S > 1) {
+    const size_t need = (size_t)pl.S * tiles * kWaves * p.hm8 * 64 * sizeof(int4);
+    if (need > ws_have) return SERQ_EWORKSPACE;         // (a column-tiling override can change the size)
+  }
+  dim3 block(kThreads);
   const bool has_lr = p.r > 0 && p.acc_out == nullptr;
   const int lrt = !has_lr ? SERQ_BF16 : p.r_dtype;     // without a compensation matrix any instantiation will do
 #define SERQ_MFMA_LAUNCH(AB, LRT) hipLaunchKernelGGL((serq_mfma_kernel<AB, LRT>), grid, block, 0, st, p)
-  if (a.abits == 8) {
-    if (lrt == SERQ_I4) SERQ_MFMA_LAUNCH(8, SERQ_I4);
-    else if (lrt == SERQ_F16) SERQ_MFMA_LAUNCH(8, SERQ_F16);
-    else SERQ_MFMA_LAUNCH(8, SERQ_BF16);
-  } else {
-    if (lrt == SERQ_I4) SERQ_MFMA_LAUNCH(4, SERQ_I4);
-    else if (lrt == SERQ_F16) SERQ_MFMA_LAUNCH(4, SERQ_F16);
-    else SERQ_MFMA_LAUNCH(4, SERQ_BF16);
+  auto launch = [&](dim3 grid) {
+    if (a.abits == 8) {
+      if (lrt == SERQ_I4) SERQ_MFMA_LAUNCH(8, SERQ_I4);
+      else if (lrt == SERQ_F16) SERQ_MFMA_LAUNCH(8, SERQ_F16);
+      else SERQ_MFMA_LAUNCH(8, SERQ_BF16);
+    } else {
+      if (lrt == SERQ_I4) SERQ_MFMA_LAUNCH(4, SERQ_I4);
+      else if (lrt == SERQ_F16) SERQ_MFMA_LAUNCH(4, SERQ_F16);
+      else SERQ_MFMA_LAUNCH(4, SERQ_BF16);
+    }
+  };
+  if (pl.S > 1) {
+    launch(dim3((unsigned)tiles, (unsigned)pl.S));     // pass 1: the slices park their INT32 tiles
+    p.reduce = 1;
   }
+  launch(dim3((unsigned)tiles));                       // the whole layer, or pass 2
 #undef SERQ_MFMA_LAUNCH
   return hipGetLastError() == hipSuccess ? SERQ_OK : SERQ_EHIP;
 }

@@ -46,12 +46,13 @@ extern "C" int serq_linear_noalloc(const void* Xq, const float* scale, int abits
                                    int64_t M, int64_t N, int64_t K,
                                    void* Y, int y_dtype, int64_t ldy, int flags, void* stream) {
   if (N > kMaxN) return SERQ_ELIMIT;
-  if (serq_workspace_bytes(M, N, K, r, abits) > sizeof(unsigned long long) * kScratchWords) return SERQ_ELIMIT;
   void* ws = nullptr;
   const int rc = scratch_for_current_device(&ws, (hipStream_t)stream);
   if (rc != SERQ_OK) return rc;
   // The kernels receive the device address as an argument, exactly as they receive a caller's workspace;
   // they return every word they used to zero before they finish, so nothing has to be cleared per call.
+  // (The array holds the decode path's meeting words only: the tiled path, which could park K slices in a
+  // larger workspace, finds none here and runs unsliced.)
   return serq_linear(Xq, scale, abits, Wq, wscale, s_begin, r, Rp, r_dtype, M, N, K, Y, y_dtype, ldy,
                      ws, sizeof(unsigned long long) * kScratchWords, flags, stream);
 }

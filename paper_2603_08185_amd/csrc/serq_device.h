@@ -222,6 +222,7 @@ struct LinearArgs {
 size_t skinny_workspace_bytes(int N);
 int launch_skinny(const LinearArgs& a, hipStream_t st);
 int launch_mfma(const LinearArgs& a, hipStream_t st);
+size_t mfma_split_workspace_bytes(int M, int N, int K, int abits, int forced);
 int launch_quantize_act(const void* X, const void* U, int x_dtype, const float* s_inv, int64_t M, int K, int64_t ldx,
                         int64_t ldu, int abits, void* Xq, float* scale, hipStream_t st);
 

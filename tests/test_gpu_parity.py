@@ -248,6 +248,56 @@ def test_gemm_i32_mfma_column_tiling_override(abits, coltiles):
         assert np.array_equal(got.cpu().numpy(), want), f"groupm={groupm}"
 
 
+def _split_ws(M, N, S):
+    # the decode path's words, then room for S parked INT32 tiles of 256 x 256 per output tile
+    n = serq.lib().serq_workspace_bytes(1, N, 64, 0, 8) + S * ((M + 255) // 256) * (N // 32) * 256 * 1024
+    ws = torch.empty(n, dtype=torch.uint8, device=DEV)
+    serq._check("serq_workspace_init", serq.lib().serq_workspace_init(serq._ptr(ws), ws.numel(), serq._stream()))
+    return ws
+
+
+# K slices of the tiled kernel (two launches: the slices park their INT32 tiles, a second pass adds them up):
+# forced through the flags on shapes with ragged K tiles, several token tiles and every column tiling
+@pytest.mark.parametrize("abits", [4, 8])
+@pytest.mark.parametrize("S", [2, 3, 5])
+@pytest.mark.parametrize("M,N,K", [(40, 96, 704), (256, 256, 1024), (300, 288, 1088), (64, 800, 2560), (513, 64, 1344),
+                                   (90, 160, 832)])
+def test_gemm_i32_mfma_k_slices(abits, S, M, N, K):
+    Xq, Wq = _codes(M, K, N, abits, seed=M + N + K + S)
+    pk, xq, _ = _device_codes(Xq, Wq, abits)
+    want = orc.gemm_i32(Xq, Wq)
+    ws = _split_ws(M, N, S)
+    for coltiles in (0, 3, 2047):
+        got = serq.gemm_i32(xq, abits, pk.Wq, M, N, K, ws=ws, flags_=serq.flags(serq.PATH_MFMA, splitk=S, coltiles=coltiles))
+        assert np.array_equal(got.cpu().numpy(), want), coltiles
+    assert not ws[:serq.lib().serq_workspace_bytes(1, N, 64, 0, 8)].any()      # the decode path's words stay clean
+
+
+@pytest.mark.parametrize("abits", [4, 8])
+@pytest.mark.parametrize("out_dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("M,K,N,r,S", [(70, 832, 64, 48, 2), (300, 1088, 288, 128, 4), (256, 2048, 96, 640, 3)])
+def test_layer_mfma_k_slices(abits, out_dtype, M, K, N, r, S):
+    # the sliced layer gives the bits of the unsliced one (integer sums), with every form of the compensation matrix
+    spec = _small_spec(abits, M, K, N, r, out_dtype=out_dtype)
+    L = workloads.make_layer(spec)
+    O = oracle_layer(spec, L)
+    pk = serq.pack_weights(L["W"].to(DEV), L["s"].to(DEV), 0, want_R=False, want_Rp=False)
+    Xq, scale = serq.quantize_act(O.Xhat.to(DEV), pk.s_inv, abits)
+    ws = _split_ws(M, N, S)
+    Y64 = orc.linear(O.Xq, O.scale, O.pk["Wq"], O.pk["wscale"], f64(L["R"]))
+    for Rp, rdt in ((serq.pack_lowrank(L["R"].to(DEV)), torch.bfloat16), (serq.pack_lowrank_q4(L["R"].to(DEV)), serq.I4),
+                    (None, torch.bfloat16)):
+        kw = dict(Rp=Rp, r=r if Rp is not None else 0, r_dtype=rdt, out_dtype=DT[out_dtype])
+        Y1 = serq.linear(Xq, scale, abits, pk.Wq, pk.wscale, M, N, K, flags_=serq.flags(serq.PATH_MFMA, splitk=1), **kw)
+        Ys = serq.linear(Xq, scale, abits, pk.Wq, pk.wscale, M, N, K, ws=ws, flags_=serq.flags(serq.PATH_MFMA, splitk=S), **kw)
+        assert torch.equal(Y1, Ys)
+        if rdt == torch.bfloat16 and Rp is not None:
+            assert_y_close(Ys, Y64, spec.name)
+    with pytest.raises(serq.SerqError) as e:           # slices asked for without the room to park them
+        serq.linear(Xq, scale, abits, pk.Wq, pk.wscale, M, N, K, flags_=serq.flags(serq.PATH_MFMA, splitk=S))
+    assert e.value.code == -5
+
+
 def test_gemm_extreme_codes_no_overflow():
     # every product at its maximum magnitude over a long K
     for abits in (4, 8):
