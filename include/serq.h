@@ -101,10 +101,11 @@ int serq_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
  *            position kp; NULL = order by saliency: channel scale
  *            max_n |W[n,k]*s[k]|, descending, ties to the lower index.
  *            A caller-supplied perm_in is TRUSTED input: it must be a
- *            permutation of 0..K-1.  It is not checked; an index out of range
- *            makes the preparation kernels read W and s out of bounds, a
- *            repeated one silently drops a channel, and the call still
- *            returns SERQ_OK (the same holds for serq_mx_pack_weights).
+ *            permutation of 0..K-1.  It is not checked: indices are clamped
+ *            into 0..K-1 (nothing is read out of bounds), but a clamped or
+ *            repeated index silently gives a wrong layer and the call still
+ *            returns SERQ_OK (the same holds for serq_mx_pack_weights and
+ *            serq_g128_pack_weights).
  *   Wq_out   serq_packed_weight_bytes(N,K) bytes.
  *   wscale_out [N] fp32: max_k |W~[n,k]| / 7 (1.0 for an all-zero row).
  *   perm_out [K] int32 (required; equals perm_in when that is given).

@@ -77,10 +77,15 @@ __global__ __launch_bounds__(kT) void rank_perm_kernel(const float* __restrict__
   perm[pos] = k;
 }
 
+// a caller's order is trusted to be a permutation; indices are clamped into [0, K) all the same, so that a bad one
+// cannot make the kernels below read outside W and s (it still gives a wrong layer)
 __global__ __launch_bounds__(kT) void copy_perm_kernel(const int32_t* __restrict__ in, int K,
                                                        int32_t* __restrict__ out) {
   const int k = blockIdx.x * kT + threadIdx.x;
-  if (k < K) out[k] = in[k];
+  if (k < K) {
+    const int v = in[k];
+    out[k] = v < 0 ? 0 : (v >= K ? K - 1 : v);
+  }
 }
 
 __global__ __launch_bounds__(kT) void sinv_kernel(const float* __restrict__ s, const int32_t* __restrict__ perm,

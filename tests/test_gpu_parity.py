@@ -140,6 +140,19 @@ def test_pack_saliency_ties_and_zero_rows():
     assert np.array_equal(serq.unpack_weights(pk.Wq, N, K).cpu().numpy(), pk_o["Wq"])
 
 
+def test_pack_clamps_a_bad_caller_order():
+    # perm_in is trusted input, but indices are clamped into range before anything is read through them
+    N, K = 32, 128
+    W = torch.randn((N, K), generator=torch.Generator().manual_seed(9)).to(DEV)
+    perm = torch.arange(K, dtype=torch.int32)
+    perm[3], perm[7] = -5, K + 10
+    pk = serq.pack_weights(W, None, 16, perm_in=perm.to(DEV))
+    got = pk.perm.cpu()
+    assert got[3] == 0 and got[7] == K - 1 and torch.equal(got[8:], perm[8:])
+    want = orc.pack_weights(W.cpu().numpy(), None, 16, perm=None)   # (only to show the call returned a layer at all)
+    assert serq.unpack_weights(pk.Wq, N, K).shape == want["Wq"].shape
+
+
 def test_pack_lowrank_roundtrip():
     for dt in (torch.float16, torch.bfloat16):
         R = torch.randn((48, 96), generator=torch.Generator().manual_seed(5)).to(dt).to(DEV)
