@@ -215,6 +215,8 @@ int serq_linear(const void* Xq, const float* scale, int abits,
  * Every call on one GPU uses that GPU's one array: calls that overlap in time on the same GPU (two
  * streams, two threads) race; calls on one stream, or otherwise ordered, are fine.  The kernels leave
  * the array zeroed when they finish, so successive calls of any size need no clearing in between.
+ * The first call on a GPU also looks the array up and clears it once (a fill kernel on `stream`): make
+ * that call before a capture begins, so that the graph records the layer's kernels only.
  */
 int serq_linear_noalloc(const void* Xq, const float* scale, int abits,
                         const void* Wq, const float* wscale,

@@ -67,3 +67,27 @@ def ulp_close(a: np.ndarray, ref64: np.ndarray, dtype: torch.dtype, ulps: float 
     tiny = {torch.float32: 2.0 ** -149, torch.float16: 2.0 ** -24, torch.bfloat16: 2.0 ** -133}[dtype]
     step = np.maximum(np.abs(ref64) * 2.0 ** (1 - mant), tiny)
     return bool(np.all(np.abs(a.astype(np.float64) - ref64) <= ulps * step))
+
+
+def replay_check(step, outputs, inputs_mutator):
+    """Run `step` eagerly, capture it, replay it three times (with eager work in between) on changed inputs."""
+    step()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for it in range(3):
+        inputs_mutator(it)
+        step()                                           # eager reference on the new inputs
+        torch.cuda.synchronize()
+        want = [o.clone() for o in outputs]
+        for o in outputs:
+            o.zero_()                                    # eager work of the program's own between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for o, w in zip(outputs, want):
+            assert torch.equal(o, w), f"replay {it} differs from the eager result"

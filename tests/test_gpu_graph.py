@@ -9,34 +9,11 @@ import torch
 
 import workloads
 from paper_2603_08185_amd import binding as serq
+from tests._util import replay_check as _replay_check
 
 pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
-
-
-def _replay_check(step, outputs, inputs_mutator):
-    """Run `step` eagerly, capture it, replay it three times (with eager work in between) on changed inputs."""
-    step()
-    torch.cuda.synchronize()
-    side = torch.cuda.Stream()
-    g = torch.cuda.CUDAGraph()
-    with torch.cuda.stream(side):
-        with torch.cuda.graph(g, stream=side):
-            step()
-    torch.cuda.synchronize()
-    for it in range(3):
-        inputs_mutator(it)
-        step()                                           # eager reference on the new inputs
-        torch.cuda.synchronize()
-        want = [o.clone() for o in outputs]
-        for o in outputs:
-            o.zero_()                                    # eager work of the program's own between the replays
-        torch.cuda.synchronize()
-        g.replay()
-        torch.cuda.synchronize()
-        for o, w in zip(outputs, want):
-            assert torch.equal(o, w), f"replay {it} differs from the eager result"
 
 
 @pytest.mark.parametrize("M,which", [(4, "down"), (16, "up"), (300, "up")])
@@ -84,3 +61,26 @@ def test_mxfp4_layer_replays(M):
         X[:, it] += 3.0
 
     _replay_check(step, [Y, Xq, xsc], mutate)
+
+
+@pytest.mark.parametrize("abits,M", [(4, 8), (8, 16), (8, 300)])
+def test_group128_layer_replays(abits, M):
+    spec = workloads.config3("up", M).with_(K=1024, N=1376, r=64, abits=abits)
+    L = workloads.make_layer(spec, want=("X", "s", "W"))
+    pk = serq.g128_pack_weights(L["W"].to(DEV), L["s"].to(DEV), spec.r)
+    X = L["X"].to(DEV).clone()
+    X0 = X.clone()
+    Xq = torch.empty(M * spec.K * abits // 8, dtype=torch.uint8, device=DEV)
+    scale = torch.empty(M, dtype=torch.float32, device=DEV)
+    zero = torch.empty(M, dtype=torch.int32, device=DEV)
+    Y = torch.empty((M, spec.N), dtype=torch.bfloat16, device=DEV)
+
+    def step():
+        serq.quantize_act_asym(X, pk.s_inv, abits, Xq=Xq, scale=scale, zero=zero)
+        serq.g128_linear(Xq, scale, zero, abits, pk.Wq, pk.gscale, pk.wsum, M, spec.N, spec.K, Rp=pk.Rp, r=spec.r, Y=Y)
+
+    def mutate(it):
+        X.copy_(X0 * (1.0 + 0.25 * it))
+        X[:, it] += 3.0
+
+    _replay_check(step, [Y, Xq, scale, zero], mutate)

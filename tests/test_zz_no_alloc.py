@@ -12,7 +12,7 @@ import torch
 import workloads
 from oracle import serq_oracle as orc
 from paper_2603_08185_amd import binding as serq
-from tests._util import DT, assert_y_close, f64, oracle_layer
+from tests._util import DT, assert_y_close, f64, oracle_layer, replay_check
 
 pytestmark = pytest.mark.gpu
 
@@ -58,3 +58,29 @@ def test_noalloc_tiled_path_and_limit():
     with pytest.raises(serq.SerqError) as e:
         serq.linear_noalloc(Xq, scale, 4, pk.Wq, pk.wscale, 1, 32768 + 32, 64, Y)
     assert e.value.code == -8
+
+
+def test_noalloc_under_graph_capture():
+    # the caller this entry point is for: one eager call first (it looks up and clears the built-in array),
+    # then the call recorded into a HIP graph and replayed on changed inputs
+    spec = workloads.LayerSpec("noalloc_graph", 9, 8, 8, 1024, 1376, 64, "bf16", "bf16", 3, 20.0, 60.0)
+    L = workloads.make_layer(spec)
+    pk = serq.pack_weights(L["W"].to(DEV), L["s"].to(DEV), 0, want_R=False, want_Rp=False)
+    Rp = serq.pack_lowrank(L["R"].to(DEV))
+    X = L["X"].to(DEV).clone()
+    X0 = X.clone()
+    Xq = torch.empty(spec.M * spec.K, dtype=torch.uint8, device=DEV)
+    scale = torch.empty(spec.M, dtype=torch.float32, device=DEV)
+    Y = torch.empty((spec.M, spec.N), dtype=torch.bfloat16, device=DEV)
+
+    def step():
+        serq.quantize_act(X, pk.s_inv, 8, Xq=Xq, scale=scale)
+        serq.linear_noalloc(Xq, scale, 8, pk.Wq, pk.wscale, spec.M, spec.N, spec.K, Y, Rp=Rp, r=spec.r)
+
+    def mutate(it):
+        X.copy_(X0 * (1.0 + 0.25 * it))
+        X[:, it] += 3.0
+
+    replay_check(step, [Y, Xq, scale], mutate)
+    ws = serq.workspace(spec.M, spec.N, spec.K, spec.r, 8, DEV)
+    assert torch.equal(Y, serq.linear(Xq, scale, 8, pk.Wq, pk.wscale, spec.M, spec.N, spec.K, Rp=Rp, r=spec.r, ws=ws))
