@@ -312,12 +312,6 @@ __device__ __forceinline__ void store_y(const GParams& p, int m, int n, const fl
 // (fp16: the fold below widens them inside a mixed-precision fused multiply-add)
 typedef _Float16 h4 __attribute__((ext_vector_type(4)));
 struct GS16 { h4 v[4]; };
-__device__ __forceinline__ GS16 load_gs16(const uint16_t* blk, int g) {
-  GS16 r;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) r.v[i] = *(const h4*)(blk + 8 * i + 4 * g);
-  return r;
-}
 // accf += gscale * acc for one 32 x 32 tile (register e: channel 8*(e/4) + 4g + e%4)
 __device__ __forceinline__ void fold_tile(const GS16& gs, const v16i& acc, v16f& accf) {
 #pragma unroll
@@ -345,17 +339,22 @@ __device__ __forceinline__ v16f mfma_lr16(const u4& r, const u4& x, v16f acc, bo
 }
 
 // ---- M <= 32: one workgroup of 8 waves per block of 32 output channels, weights streamed once ----------
-// Wave w takes the groups w, w+8, ... two at a time: the four 1-KiB weight fragments, the two groups' scales
-// and the token codes are all requested before the first is used.  Each group's INT32 tile is folded into
-// the wave's fp32 tile, the wave adds its share of the rank-r term, and the eight waves are added through
-// LDS in a fixed order (run-to-run identical).
-constexpr int kPitch = 36;
+// Wave w takes the groups w, w+8, ... NG at a time (2, or 4 for K >= 8192, where a wave still has two rounds
+// of them: measured better from there on, worse below): the 1-KiB weight fragments, the groups' scales and
+// the token codes are all requested before the first is used.  The tokens are the MFMA's row operand
+// and the weights its column operand, so a lane holds ONE output channel (one group scale per lane) and
+// its registers are tokens: register e of lane (c, g) is token 8*(e/4) + 4g + e%4 of channel c.  With M <= 8
+// tokens only registers 0..3 carry anything, with M <= 16 registers 0..7, ...: the fold of a group's INT32
+// tile into the fp32 tile touches 4*MQ registers (MQ = ceil(M/8)), not 16.  The wave adds its share of the
+// rank-r term, and the eight waves are added through LDS in a fixed order (run-to-run identical).
+constexpr int kPitch = 33;
 constexpr int kSkinnyWaves = 8;
-template <int ABITS>
+template <int ABITS, int MQ, int NG>
 __global__ __launch_bounds__(64 * kSkinnyWaves) void serq_g128_skinny_kernel(const GParams p) {
   constexpr int SH = ABITS == 8 ? 4 : 8;
   constexpr float kInv = 1.0f / (float)(1 << SH);
-  __shared__ float red[kSkinnyWaves][32 * kPitch];
+  constexpr int NE = 4 * MQ;                                // live accumulator registers
+  __shared__ float red[kSkinnyWaves][8 * MQ * kPitch];
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, m = l & 31, g = l >> 5;
   const int nb = blockIdx.x;
   const int KB = p.K >> 6, G = p.K >> 7;
@@ -363,12 +362,13 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void serq_g128_skinny_kernel(con
   const bool mv = m < p.M;
   const uint8_t* xrow = p.Xq + (size_t)(mv ? m : 0) * rowbytes;
   const u4* wfr = p.Wq + (size_t)nb * KB * 64 + l;
-  const uint16_t* gsb = p.gsc + (size_t)nb * G * 32;
+  const uint16_t* gsl = p.gsc + (size_t)nb * G * 32 + m;    // this lane's channel (lane & 31)
   const int zm = (p.zero && mv) ? p.zero[m] : 0;
+  const v16i kZero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
-  v16f accf;
+  float accf[NE];
 #pragma unroll
-  for (int e = 0; e < 16; ++e) accf[e] = 0.0f;
+  for (int e = 0; e < NE; ++e) accf[e] = 0.0f;
   // the token operands of fragment fr: two int8x16 pieces (8-bit) or one packed piece (4-bit); zero without a token
   auto load_x = [&](int fr, u4& x0, u4& x1) {
     x0 = u4{0u, 0u, 0u, 0u};
@@ -383,10 +383,8 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void serq_g128_skinny_kernel(con
       }
     }
   };
-  auto group_mfma = [&](const u4& wa, const u4& wb, const u4 (&x)[4], const GS16& gs) {
+  auto group_mfma = [&](const u4& wa, const u4& wb, const u4 (&x)[4], _Float16 gs) {
     v16i acc;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[e] = 0;
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       v4i a0, a1, b0, b1;
@@ -397,29 +395,31 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void serq_g128_skinny_kernel(con
       } else {
         unpack_frag(x[2 * u], b0, b1);
       }
-      acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, acc, 0, 0, 0);
+      // tokens first: rows of the result are tokens, columns (lanes) are channels; the group starts from zero
+      if (u == 0) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(b0, a0, kZero16, 0, 0, 0);
+      else acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(b0, a0, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(b1, a1, acc, 0, 0, 0);
     }
-    fold_tile(gs, acc, accf);
+#pragma unroll
+    for (int e = 0; e < NE; ++e) accf[e] = __builtin_fmaf((float)gs, (float)acc[e], accf[e]);
   };
 #pragma unroll 1
-  for (int grp = w; grp < G; grp += 2 * kSkinnyWaves) {
-    const int grp2 = grp + kSkinnyWaves;
-    const bool two = grp2 < G;                            // uniform over the wave
-    const int gb = two ? grp2 : grp;                      // a wave without a second group repeats the first (unused)
-    const u4 w0 = __builtin_nontemporal_load(&wfr[(size_t)(2 * grp) * 64]);
-    const u4 w1 = __builtin_nontemporal_load(&wfr[(size_t)(2 * grp + 1) * 64]);
-    const u4 w2 = __builtin_nontemporal_load(&wfr[(size_t)(2 * gb) * 64]);
-    const u4 w3 = __builtin_nontemporal_load(&wfr[(size_t)(2 * gb + 1) * 64]);
-    u4 xa[4], xb[4];
-    load_x(2 * grp, xa[0], xa[1]);
-    load_x(2 * grp + 1, xa[2], xa[3]);
-    load_x(2 * gb, xb[0], xb[1]);
-    load_x(2 * gb + 1, xb[2], xb[3]);
-    const GS16 gsa = load_gs16(gsb + (size_t)grp * 32, g);
-    const GS16 gsb2 = load_gs16(gsb + (size_t)gb * 32, g);
-    group_mfma(w0, w1, xa, gsa);
-    if (two) group_mfma(w2, w3, xb, gsb2);
+  for (int grp = w; grp < G; grp += NG * kSkinnyWaves) {
+    u4 wv[NG][2], xv[NG][4];
+    _Float16 gsv[NG];
+#pragma unroll
+    for (int q = 0; q < NG; ++q) {
+      const int gq = grp + q * kSkinnyWaves;
+      const int gb = gq < G ? gq : grp;                   // a wave without a q-th group repeats the first (unused)
+      wv[q][0] = __builtin_nontemporal_load(&wfr[(size_t)(2 * gb) * 64]);
+      wv[q][1] = __builtin_nontemporal_load(&wfr[(size_t)(2 * gb + 1) * 64]);
+      load_x(2 * gb, xv[q][0], xv[q][1]);
+      load_x(2 * gb + 1, xv[q][2], xv[q][3]);
+      gsv[q] = __builtin_bit_cast(_Float16, gsl[(size_t)gb * 32]);
+    }
+#pragma unroll
+    for (int q = 0; q < NG; ++q)
+      if (grp + q * kSkinnyWaves < G) group_mfma(wv[q][0], wv[q][1], xv[q], gsv[q]);   // uniform over the wave
   }
   // rank-r term on the re-centred codes, added to the wave's tile
   const bool has_lr = p.r > 0 && p.Rp != nullptr;
@@ -433,23 +433,20 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void serq_g128_skinny_kernel(con
     for (int jb = w; jb < JB; jb += kSkinnyWaves) {
       const u4 rr = rfr[(size_t)jb * 64];
       const u4 xf = lr_operand<ABITS>(xrow, p.s_begin + 16 * jb + 8 * g, zm, mv, bf);
-      accl = mfma_lr16(rr, xf, accl, bf);
+      accl = mfma_lr16(xf, rr, accl, bf);
     }
 #pragma unroll
-    for (int e = 0; e < 16; ++e) accf[e] = __builtin_fmaf(accf[e], kInv, accl[e]);   // 2^-SH: exact
+    for (int e = 0; e < NE; ++e) accf[e] = __builtin_fmaf(accf[e], kInv, accl[e]);   // 2^-SH: exact
   } else {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) accf[e] *= kInv;
+    for (int e = 0; e < NE; ++e) accf[e] *= kInv;
   }
-  // combine: register 4i+e of lane (m,g) is channel 8i + 4g + e of token m
-  if (mv) {
+  // combine: register 4i+e of lane (c,g) is token 8i + 4g + e of channel c
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      *(float4*)&red[w][m * kPitch + 8 * i + 4 * g] = make_float4(accf[4 * i], accf[4 * i + 1], accf[4 * i + 2], accf[4 * i + 3]);
-  }
+  for (int e = 0; e < NE; ++e) red[w][(8 * (e >> 2) + 4 * g + (e & 3)) * kPitch + m] = accf[e];
   __syncthreads();
 #pragma unroll
-  for (int q = 0; q < 1024 / (64 * kSkinnyWaves); ++q) {
+  for (int q = 0; q < 256 * MQ / (64 * kSkinnyWaves) + (256 * MQ % (64 * kSkinnyWaves) ? 1 : 0); ++q) {
     const int id = tid + q * 64 * kSkinnyWaves;
     const int nl = id & 31, mt = id >> 5;
     if (mt >= p.M) continue;
@@ -467,20 +464,29 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void serq_g128_skinny_kernel(con
 }
 
 // ---- M > 32: LDS-tiled kernel, 128 tokens x 128 channels per workgroup of 4 waves (2 x 2) ----------------
-// One stage = one group of 128 input channels: 4 blocks x 2 weight fragments (8 KiB) and 128 token rows
+// One stage = one group of 128 input channels: 4 blocks x 2 weight fragments (8 KiB), 128 token rows
 // (16 KiB at 8 bits, 8 KiB at 4 bits; 16-byte pieces xor-swizzled per row so that the operand reads are
-// free of bank conflicts).  Two stages: the next group travels global -> registers while the current one
-// is multiplied, and is written to the other stage before the one barrier of the iteration.  Each wave
-// owns 2 x 2 MFMA tiles: 64 INT32 accumulators, folded into 64 fp32 accumulators after every group.
+// free of bank conflicts) and the group's 128 scales (256 B).  The stages form a ring (3 deep at 8 bits,
+// 4 at 4 bits) filled by direct global -> LDS loads (no staging registers) that run two or three groups
+// ahead of the arithmetic and are counted by hand with vmcnt; one barrier per group.  Two workgroups
+// share a compute unit, so the barrier of one is covered by the other.
+// Each wave owns 2 x 2 MFMA tiles: 64 INT32 accumulators, folded into 64 fp32 accumulators after every
+// group.  The four MFMAs of a group run tile by tile, and the convert-and-FMA pairs that fold the tile
+// finished before are issued between them, so that the vector unit works in the shadow of the matrix
+// unit (a group costs as many cycles on the one as on the other).
 template <int ABITS>
 struct GTile {
   static constexpr int XROW = 128 * ABITS / 8;       // bytes of a token's 128 codes
   static constexpr int P = XROW / 16;                // 16-byte pieces per token row: 8 or 4
   static constexpr int WB = 4 * 2 * 1024;
   static constexpr int XB = 128 * XROW;
-  static constexpr int STAGE = WB + XB;
-  static constexpr int NX = 128 * P / 256;           // token pieces per thread: 4 or 2
+  static constexpr int SC_OFF = WB + XB;             // 4 blocks x 32 fp16 scales
+  static constexpr int STAGE = SC_OFF + 256;
+  static constexpr int NS = ABITS == 8 ? 3 : 4;      // ring depth
+  static constexpr int NLX = 128 * P / 256;          // token loads per thread and group: 4 or 2
+  static constexpr int NL = 2 + NLX + 1;             // direct loads per wave and group
   static __device__ __forceinline__ int swz(int row) { return ABITS == 8 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
+  static_assert(2 * NS * STAGE <= 160 * 1024, "two workgroups per compute unit");
 };
 
 template <int ABITS>
@@ -488,7 +494,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   using T = GTile<ABITS>;
   constexpr int SH = ABITS == 8 ? 4 : 8;
   constexpr float kInv = 1.0f / (float)(1 << SH);
-  __shared__ __align__(16) uint8_t lds[2 * T::STAGE];
+  constexpr int NS = T::NS;
+  __shared__ __align__(16) uint8_t lds[NS * T::STAGE];
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, lm = l & 31, g = l >> 5;
   const int wn = w & 1, wm = w >> 1;
   const int NB = p.N >> 5, KB = p.K >> 6, G = p.K >> 7;
@@ -502,40 +509,39 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int mrows = p.M - m0 < 128 ? p.M - m0 : 128;
   const size_t rowbytes = (size_t)p.K * ABITS / 8;
 
-  // what this thread carries from global memory to a stage
-  const u4* wsrc[2];
-  int wdst[2];
+  // ---- what this wave sends from global memory into a stage ---------------------------------------
+  // A direct load puts the 16 bytes of lane l at (wave-uniform LDS base) + 16 l, so the swizzle of the
+  // token pieces is applied on the source side.  Per group and wave: 2 weight fragments, NLX x 64 token
+  // pieces, and (4 lanes) the 64 bytes of scales of block w.
+  const int wu = __builtin_amdgcn_readfirstlane(w);
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_addr(lds));
+  uint32_t wv[2], xv[T::NLX];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int pc = tid + 256 * i;                     // [block][fragment][lane]
     int b = pc >> 7;
     b = b < nbt ? b : nbt - 1;                        // blocks past the tile: duplicates, never stored
-    wsrc[i] = p.Wq + ((size_t)(nb0 + b) * KB + ((pc >> 6) & 1)) * 64 + (pc & 63);
-    wdst[i] = pc * 16;
+    wv[i] = (uint32_t)((b * KB + ((pc >> 6) & 1)) * 1024 + (pc & 63) * 16);
   }
-  const uint8_t* xsrc[T::NX];
-  int xdst[T::NX];
 #pragma unroll
-  for (int i = 0; i < T::NX; ++i) {
-    const int q = tid + 256 * i;
-    const int row = q / T::P, c = q % T::P;
+  for (int i = 0; i < T::NLX; ++i) {
+    const int q = tid + 256 * i;                      // LDS piece: row q / P, slot q % P
+    const int row = q / T::P;
+    const int c = (q % T::P) ^ T::swz(row);           // the global piece that lives in that slot
     const int rr = row < mrows ? row : mrows - 1;     // rows past M: duplicates, never stored
-    xsrc[i] = p.Xq + (size_t)(m0 + rr) * rowbytes + 16 * c;
-    xdst[i] = T::WB + row * T::XROW + 16 * (c ^ T::swz(row));
+    xv[i] = (uint32_t)((size_t)rr * rowbytes) + 16u * c;
   }
-  u4 wreg[2], xreg[T::NX];
-  auto fetch = [&](int gi) {
+  const uint32_t sv = (uint32_t)((wu < nbt ? wu : nbt - 1) * G * 64 + (l & 3) * 16);
+  const uint8_t* wbase = (const uint8_t*)p.Wq + (size_t)nb0 * KB * 1024;
+  const uint8_t* xbase = p.Xq + (size_t)m0 * rowbytes;
+  const uint8_t* sbase = (const uint8_t*)p.gsc + (size_t)nb0 * G * 64;
+  auto issue = [&](int gi, int st) {
+    const uint32_t sb = lds0 + (uint32_t)st * T::STAGE;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) wreg[i] = wsrc[i][(size_t)(2 * gi) * 64];
+    for (int i = 0; i < 2; ++i) dma16(wbase + (size_t)gi * 2048, wv[i], sb + 1024 * wu + 4096 * i);
 #pragma unroll
-    for (int i = 0; i < T::NX; ++i) xreg[i] = *(const u4*)(xsrc[i] + (size_t)gi * T::XROW);
-  };
-  auto park = [&](int st) {
-    uint8_t* s = lds + st * T::STAGE;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) *(u4*)(s + wdst[i]) = wreg[i];
-#pragma unroll
-    for (int i = 0; i < T::NX; ++i) *(u4*)(s + xdst[i]) = xreg[i];
+    for (int i = 0; i < T::NLX; ++i) dma16(xbase + (size_t)gi * T::XROW, xv[i], sb + T::WB + 1024 * wu + 4096 * i);
+    if (l < 4) dma16(sbase + (size_t)gi * 64, sv, sb + T::SC_OFF + 64 * wu);
   };
 
   // this wave's blocks 2*wn + i and token rows 32*(2*wm + j) + lm
@@ -546,7 +552,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     xoff[j] = T::WB + row * T::XROW;
     xsw[j] = T::swz(row);
   }
-  int bi[2];                                          // block index in the layer, clamped for the scale loads
+  int bi[2];                                          // block index in the layer, clamped for the loads of the epilogue
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int b = 2 * wn + i;
@@ -562,51 +568,68 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) { acc[i][j][e] = 0; accf[i][j][e] = 0.0f; }
+  GS16 gprev;                                         // scales of the tiles whose fold is still owed: block 1 of the group before
+#pragma unroll
+  for (int q4 = 0; q4 < 4; ++q4) gprev.v[q4] = h4{0, 0, 0, 0};
 
-  fetch(0);
-  park(0);
-  __syncthreads();
+  // the four MFMAs of tile (i,j) of a group, each followed by a quarter of the fold of tile `fa` into `ff`
+  auto tile = [&](const v4i (&a)[4], const v4i (&b)[4], v16i& t_acc, const GS16& fg, const v16i& fa, v16f& ff) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      // the first product of a group starts from zero (a constant operand, no registers to clear)
+      if (t == 0) t_acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[t], b[t], kZero16, 0, 0, 0);
+      else t_acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[t], b[t], t_acc, 0, 0, 0);
+#pragma unroll
+      for (int e = 4 * t; e < 4 * t + 4; ++e) ff[e] = __builtin_fmaf((float)fg.v[e >> 2][e & 3], (float)fa[e], ff[e]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < G) issue(s, s);
+  int st = 0, sti = NS - 1;
 #pragma unroll 1
   for (int gi = 0; gi < G; ++gi) {
-    const bool more = gi + 1 < G;
-    if (more) fetch(gi + 1);
+    // group gi has landed (this wave's loads: all but those of the NS-2 groups behind it), every wave has
+    // got here, so everybody's loads have landed and the stage read last round may be refilled
+    const int last = gi + NS - 2 < G - 1 ? gi + NS - 2 : G - 1;
+    if (last - gi == NS - 2) wait_dma_barrier<(NS - 2) * T::NL>();
+    else wait_dma_barrier<0>();
+    if (gi + NS - 1 < G) issue(gi + NS - 1, sti);
+    sti = sti + 1 == NS ? 0 : sti + 1;
+    const uint8_t* s = lds + st * T::STAGE;
+    st = st + 1 == NS ? 0 : st + 1;
+    v4i a[2][4], b[2][4];                             // operands of the group's four 32-channel steps
     GS16 gs[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) gs[i] = load_gs16(p.gsc + ((size_t)bi[i] * G + gi) * 32, g);
-    const uint8_t* s = lds + (gi & 1) * T::STAGE;
+    for (int i = 0; i < 2; ++i) {
 #pragma unroll
-    for (int f = 0; f < 2; ++f) {
-      v4i a0[2], a1[2], b0[2], b1[2];
+      for (int f = 0; f < 2; ++f)
+        unpack_frag(*(const u4*)(s + (((2 * wn + i) * 2 + f) * 64 + l) * 16), a[i][2 * f], a[i][2 * f + 1]);
+      const int j = i;
 #pragma unroll
-      for (int i = 0; i < 2; ++i) unpack_frag(*(const u4*)(s + (((2 * wn + i) * 2 + f) * 64 + l) * 16), a0[i], a1[i]);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int f = 0; f < 2; ++f) {
         if constexpr (ABITS == 8) {
           const int c = 4 * f + 2 * g;
-          b0[j] = *(const v4i*)(s + xoff[j] + 16 * (c ^ xsw[j]));
-          b1[j] = *(const v4i*)(s + xoff[j] + 16 * ((c + 1) ^ xsw[j]));
+          b[j][2 * f] = *(const v4i*)(s + xoff[j] + 16 * (c ^ xsw[j]));
+          b[j][2 * f + 1] = *(const v4i*)(s + xoff[j] + 16 * ((c + 1) ^ xsw[j]));
         } else {
-          unpack_frag(*(const u4*)(s + xoff[j] + 16 * ((2 * f + g) ^ xsw[j])), b0[j], b1[j]);
+          unpack_frag(*(const u4*)(s + xoff[j] + 16 * ((2 * f + g) ^ xsw[j])), b[j][2 * f], b[j][2 * f + 1]);
         }
       }
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          // the first product of a group starts from zero (a constant operand, no registers to clear)
-          if (f == 0) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[i], b0[j], kZero16, 0, 0, 0);
-          else acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[i], b0[j], acc[i][j], 0, 0, 0);
-          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[i], b1[j], acc[i][j], 0, 0, 0);
-        }
+      for (int q4 = 0; q4 < 4; ++q4) gs[i].v[q4] = *(const h4*)(s + T::SC_OFF + 64 * (2 * wn + i) + 2 * (8 * q4 + 4 * g));
     }
-    // fold the group's INT32 tile into the fp32 tile with the group's scales
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j) fold_tile(gs[i], acc[i][j], accf[i][j]);
-    if (more) park((gi + 1) & 1);
-    __syncthreads();
+    // each tile's MFMAs shadow the fold of the tile finished two tiles earlier (its results have long arrived);
+    // the two tiles of block 1 are folded during the first half of the next group
+    tile(a[0], b[0], acc[0][0], gprev, acc[1][0], accf[1][0]);
+    tile(a[0], b[1], acc[0][1], gprev, acc[1][1], accf[1][1]);
+    tile(a[1], b[0], acc[1][0], gs[0], acc[0][0], accf[0][0]);
+    tile(a[1], b[1], acc[1][1], gs[0], acc[0][1], accf[0][1]);
+    gprev = gs[1];
   }
+  fold_tile(gprev, acc[1][0], accf[1][0]);
+  fold_tile(gprev, acc[1][1], accf[1][1]);
 
   // ---- epilogue: zero point, rank-r term on the re-centred codes, token scale, one store ----------------
   const bool has_lr = p.r > 0 && p.Rp != nullptr;
@@ -781,8 +804,22 @@ int serq_g128_linear(const void* Xq, const float* scale, const int32_t* zero, in
   const bool skinny = path == SERQ_PATH_SKINNY || (path == SERQ_PATH_AUTO && M <= 32);
   if (skinny) {
     dim3 grid((unsigned)(N / 32));
-    if (abits == 8) hipLaunchKernelGGL(serq_g128_skinny_kernel<8>, grid, dim3(64 * kSkinnyWaves), 0, st, p);
-    else hipLaunchKernelGGL(serq_g128_skinny_kernel<4>, grid, dim3(64 * kSkinnyWaves), 0, st, p);
+    // specialised on ceil(M / 8): the number of accumulator register quads that hold tokens
+#define SERQ_G128_SKINNY(AB, MQ)                                                                                   \
+  do {                                                                                                             \
+    if (deep) hipLaunchKernelGGL((serq_g128_skinny_kernel<AB, MQ, 4>), grid, dim3(64 * kSkinnyWaves), 0, st, p);   \
+    else hipLaunchKernelGGL((serq_g128_skinny_kernel<AB, MQ, 2>), grid, dim3(64 * kSkinnyWaves), 0, st, p);        \
+  } while (0)
+    const int mq = (int)((M + 7) / 8);
+    const bool deep = K / kGroup >= 64;                   // four groups in flight per wave pay once a wave has two rounds of them
+    if (abits == 8) {
+      if (mq == 1) SERQ_G128_SKINNY(8, 1); else if (mq == 2) SERQ_G128_SKINNY(8, 2);
+      else if (mq == 3) SERQ_G128_SKINNY(8, 3); else SERQ_G128_SKINNY(8, 4);
+    } else {
+      if (mq == 1) SERQ_G128_SKINNY(4, 1); else if (mq == 2) SERQ_G128_SKINNY(4, 2);
+      else if (mq == 3) SERQ_G128_SKINNY(4, 3); else SERQ_G128_SKINNY(4, 4);
+    }
+#undef SERQ_G128_SKINNY
   } else {
     const long long tiles = (long long)((N / 32 + 3) / 4) * ((M + 127) / 128);
     if (tiles > 0x7fffffffLL) return SERQ_ESHAPE;
