@@ -282,18 +282,22 @@ int serq_mx_unpack_weights(const void* Wq, const uint8_t* wscale, int64_t N, int
 int serq_mx_unpack_act(const void* Xq, const uint8_t* xscale, int64_t M, int64_t K,
                        uint8_t* codes_out, uint8_t* exps_out, void* stream);
 
-/* Bytes of workspace serq_mx_linear can use for this call (0: none).  Same rules as serq_workspace_bytes /
- * serq_workspace_init: zero it once after allocation, the kernel leaves it zeroed; two calls that share a
- * workspace must not overlap in time. */
+/* Bytes of workspace serq_mx_linear can use for this call.  Same rules as serq_workspace_bytes /
+ * serq_workspace_init: zero it once after allocation; two calls that share a workspace must not overlap in
+ * time.  The first part (the size this returns for M = 1) holds the words in which the decode kernel's K
+ * slices meet, and the kernel leaves it zeroed; for M > 32 a second part behind it holds the fp32 tiles the
+ * tiled kernel parks when it cuts K (few tokens, long K), which is scratch: written before it is read. */
 size_t serq_mx_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 /* The MXFP4 layer.  Y [M,N] in y_dtype, row stride ldy (multiple of 8, >= N); fp32 accumulation over
  * k in the order of the hardware's 64-channel steps, the compensation sum added to the same
  * accumulators.  s_begin is a multiple of 256 with s_begin + 64*ceil(r/64) <= K; r a multiple of 32;
- * Rq may be NULL (no compensation).  workspace may be NULL: the decode kernel then never slices K; with
- * it, layers with few blocks of 32 output channels and a long K are cut into K slices whose partial sums are
- * added in a fixed order, so results do not vary from run to run, but they depend on the number of slices
- * (fp32 addition).  flags: SERQ_PATH_* | SERQ_FLAG_SPLITK | SERQ_FLAG_COLTILES.  M = 0 is a no-op. */
+ * Rq may be NULL (no compensation).  workspace may be NULL: K is then never sliced; with it, layers that
+ * would leave most compute units idle (decode: few blocks of 32 output channels; tiled kernel: few tokens)
+ * and have a long K are cut into K slices whose partial sums are added in a fixed order, so results do not
+ * vary from run to run, but they depend on the number of slices (fp32 addition).  SERQ_FLAG_SPLITK: 0 the
+ * library's choice, 1 none, n > 1 exactly n (SERQ_EWORKSPACE if the workspace is missing or too small).
+ * flags: SERQ_PATH_* | SERQ_FLAG_SPLITK | SERQ_FLAG_COLTILES.  M = 0 is a no-op. */
 int serq_mx_linear(const void* Xq, const uint8_t* xscale, const void* Wq, const uint8_t* wscale,
                    int s_begin, int r, const void* Rq, const uint8_t* rscale,
                    int64_t M, int64_t N, int64_t K,

@@ -328,7 +328,7 @@ int serq_mx_unpack_act(const void* Xq, const uint8_t* xscale, int64_t M, int64_t
 
 size_t serq_mx_workspace_bytes(int64_t M, int64_t N, int64_t K) {
   if (M < 0 || check_nk(N, K) != SERQ_OK) return 0;
-  return M <= 32 ? skinny_mx_workspace_bytes((int)N) : 0;
+  return skinny_mx_workspace_bytes((int)N) + (M > 32 ? mx_split_workspace_bytes((int)M, (int)N, (int)K, 0) : 0);
 }
 
 int serq_mx_linear(const void* Xq, const uint8_t* xscale, const void* Wq, const uint8_t* wscale,

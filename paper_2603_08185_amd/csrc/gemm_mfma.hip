@@ -720,60 +720,6 @@ void serq_mfma_kernel(const MfmaParams p) {
 
 }  // namespace
 
-// ---- K slicing: when and how (host side) ---------------------------------------------------------
-// A layer with few tokens gives few tiles: one token tile x the column tiles.  Narrow column tiles fill more
-// compute units but every one of them walks all of K re-reading its whole token panel from LDS, so the step
-// gets no cheaper; cutting K into S slices instead multiplies the workgroups by S at the price of parking
-// S INT32 tiles per output tile and a second launch that adds them up.  The plan below prices both with a
-// small model fitted to measurements (cycles of one 64-channel step of a tile of b channel blocks; 5 TB/s for
-// the parked tiles, written and read once; 3 us for the second launch) and slices only when that wins.
-struct SplitPlan { int C, wide, nwide, S; };
-
-inline float step_cycles(int b, int abits) {
-  const float mfma = 128.0f * b, lds = abits == 8 ? 40.0f * b + 384.0f : 40.0f * b + 192.0f;
-  return 1.3f * (mfma > lds ? mfma : lds);
-}
-
-inline SplitPlan plan_split(int M, int N, int K, int abits, int ncu, int forced) {
-  const int NB = N / 32, tiles_m = (M + BM - 1) / BM;
-  const int CHh = abits == 8 ? 2 : 4;
-  const int KT = (K / 64 + CHh - 1) / CHh;             // main tiles
-  SplitPlan best;
-  plan_columns(tiles_m, NB, ncu, best.C, best.wide, best.nwide);
-  best.S = 1;
-  if (forced == 1) return best;
-  if (forced > 1) {
-    best.S = forced < KT ? forced : KT;
-    return best;
-  }
-  if ((long long)tiles_m * best.C * 4 >= 3LL * ncu || M > 512 || KT < 8) return best;   // the tiles fill the part well enough
-  const float steps = (float)(K / 64);
-  auto cost = [&](int C, int wide, int S) {
-    const long long wg = (long long)tiles_m * C * S;
-    const float rounds = (float)((wg + ncu - 1) / ncu);
-    float us = rounds * (steps / S) * step_cycles(wide, abits) / 2000.0f;
-    if (S > 1) us += 2.0f * ((float)S * M * N * 4.0f) / 5.0e6f + 3.0f;
-    return us;
-  };
-  float bc = cost(best.C, best.wide, 1);
-  const int cand[] = {2, 3, 4, 6, 8, 12, 16};
-  for (int wide = 1; wide <= 8; ++wide) {
-    const int C = (NB + wide - 1) / wide;
-    const int w2 = (NB + C - 1) / C;                    // the width this many tiles really have
-    for (int S : cand) {
-      if (S * 2 > KT || (long long)tiles_m * C * S > 2LL * ncu) continue;
-      const float c = cost(C, w2, S);
-      if (c < bc * 0.9f) {                              // only for a clear win: the model is rough
-        bc = c;
-        best.C = C; best.wide = w2; best.nwide = NB - C * (w2 - 1); best.S = S;
-      }
-    }
-  }
-  return best;
-}
-
-inline int wave_blocks8(int wide) { const int h = (wide + 1) / 2; return 8 * (h < 1 ? 1 : h); }
-
 // bytes of workspace the sliced path needs for this call (0: not sliced); `forced` as LinearArgs::splitk
 size_t mfma_split_workspace_bytes(int M, int N, int K, int abits, int forced) {
   if (M <= 0) return 0;

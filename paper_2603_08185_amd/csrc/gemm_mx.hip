@@ -50,6 +50,15 @@ struct MxParams {
   void* Y; int y_dtype; int64_t ldy;
   int tiles_m, tiles_n, groupm;
   int wide, nwide;
+  // K slicing for layers whose tiles alone leave most compute units idle (two launches of this kernel):
+  //   pass 1 (kslices > 1, reduce = 0): grid (tiles, kslices); workgroup (tile, s) multiplies slice s of the main
+  //     tiles and parks its fp32 tile in `part`, in register order (every store a full 1-KiB wave row);
+  //   pass 2 (reduce = 1): grid (tiles); no main tiles -- the accumulators start as the sum of the parked tiles,
+  //     added in slice order (the result depends on the number of slices, not on the run), then the
+  //     compensation tiles and the usual epilogue.
+  int kslices, reduce;
+  float4* part;           // [kslices][tiles][8 waves][hm8][64 lanes]
+  int hm8;                // 8 x the largest number of channel blocks a wave owns
 };
 
 
@@ -72,9 +81,20 @@ void serq_mx_kernel(const MxParams p) {
   const int blk0 = __builtin_amdgcn_readfirstlane(wn ? half : 0);
   const int nbw = __builtin_amdgcn_readfirstlane(wn ? nbt - half : half);
   const int KB = p.K >> 6;                           // weight fragments per channel block
-  const int KT = (KB + CH - 1) / CH;                 // main tiles (the last one may be partial)
-  const int KTF = KB / CH;                           // full main tiles
-  const int FR = (p.r + 63) >> 6;                    // fragments of the compensation matrix per channel block
+  const int KTg = (KB + CH - 1) / CH;                // main tiles of the layer (the last one may be partial)
+  // the main tiles [ta, tb) this workgroup multiplies: all of them, one K slice (pass 1), or none (pass 2)
+  const bool part_out = p.kslices > 1 && !p.reduce;
+  int ta = 0, tb = KTg;
+  if (part_out) {
+    const int per = KTg / p.kslices, rem = KTg % p.kslices, sl = blockIdx.y;
+    ta = sl * per + (sl < rem ? sl : rem);
+    tb = ta + per + (sl < rem ? 1 : 0);
+  } else if (p.reduce) {
+    tb = 0;
+  }
+  const int KT = tb - ta;                            // this workgroup's main tiles
+  const int KTF = (tb < KB / CH ? tb : KB / CH) - ta;   // the full ones among them (all but, possibly, the layer's last)
+  const int FR = part_out ? 0 : (p.r + 63) >> 6;     // fragments of the compensation matrix per channel block
   const int LT = (FR + CH - 1) / CH;
   const int TT = KT + LT;
   const uint32_t rowbytes = (uint32_t)p.K >> 1;
@@ -87,7 +107,7 @@ void serq_mx_kernel(const MxParams p) {
   const uint8_t* wbase = (const uint8_t*)p.Wq + (size_t)nb0 * KB * 1024;
 
   const uint8_t* xsbase = p.xsc + (size_t)m0 * 8;
-  const uint8_t* wsbase = p.wsc + (size_t)nb0 * KT * 256;
+  const uint8_t* wsbase = p.wsc + (size_t)nb0 * KTg * 256;
 
   // k-th direct load (k < 9; the 9th brings the scales) of tile t of the sequence into
   // stage st.  FULL: a main tile with all four fragments.  Otherwise every fragment / piece past the
@@ -103,7 +123,8 @@ void serq_mx_kernel(const MxParams p) {
     const bool lr = !FULL && t >= KT;
     const int lt = t - KT;
     const int KBs = lr ? FR : KB;                    // fragments per channel block in the source
-    const int f0 = lr ? CH * lt : CH * t;            // first fragment of the tile
+    const int tg = ta + t;                           // a main tile's index in the layer
+    const int f0 = lr ? CH * lt : CH * tg;           // first fragment of the tile
     const int nf = FULL ? CH : (KBs - f0 < CH ? KBs - f0 : CH);
     if (k < 4) {
       // weights: wave w fetches slots f = 8*k + w of the stage, f = nbl*CH + ch
@@ -115,7 +136,7 @@ void serq_mx_kernel(const MxParams p) {
       dma16(wsrc + (size_t)(nbl * KBs + ch) * 1024, (uint32_t)ll * 16u, sb + kWaves * 1024 * k);
     } else if (k < 8) {
       // tokens: LDS piece pc = 512*(k-4) + tid -> row pc/8, slot pc%8 holds global piece slot ^ swizzle(row)
-      const uint8_t* xsrc = lr ? xbase + (p.s_begin >> 1) + (size_t)lt * 128 : xbase + (size_t)t * 128;
+      const uint8_t* xsrc = lr ? xbase + (p.s_begin >> 1) + (size_t)lt * 128 : xbase + (size_t)tg * 128;
       const int pc = (k - 4) * kThreads + tl;
       int row = pc >> 3;
       int c = (pc & 7) ^ ((row >> 1) & 7);
@@ -130,12 +151,12 @@ void serq_mx_kernel(const MxParams p) {
       // costlier would be compiled into a branch)
       const int q = wu & 3;
       const bool tok = q < 2;
-      const int tx = lr ? (p.s_begin >> 8) + lt : t; // 256-channel tile of the token-scale array
+      const int tx = lr ? (p.s_begin >> 8) + lt : tg; // 256-channel tile of the token-scale array
       int rp = 64 * q + ll;
       const int rplast = (mrows - 1) >> 1;
       rp = rp < rplast ? rp : rplast;
-      const int Ts = lr ? LT : KT;                   // scale tiles per channel block in the source
-      const uint8_t* wsrc_main = wsbase + (size_t)t * 256;
+      const int Ts = lr ? LT : KTg;                  // scale tiles per channel block in the source
+      const uint8_t* wsrc_main = wsbase + (size_t)tg * 256;
       const uint8_t* wsrc_lr = p.rsc + ((size_t)nb0 * LT + lt) * 256;
       const uint8_t* wssrc = lr ? wsrc_lr : wsrc_main;
       const uint8_t* xssrc = xsbase + (size_t)tx * Mp * 8;
@@ -155,7 +176,7 @@ void serq_mx_kernel(const MxParams p) {
     for (int k = 0; k < 9; ++k) issue_one(std::false_type{}, t, st, k);
   };
   auto frags_of = [&](int t) {                       // valid fragments of tile t
-    const int left = t < KT ? KB - CH * t : FR - CH * (t - KT);
+    const int left = t < KT ? KB - CH * (ta + t) : FR - CH * (t - KT);
     return left < CH ? left : CH;
   };
 
@@ -200,6 +221,33 @@ void serq_mx_kernel(const MxParams p) {
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+    // register (i, j, q4) of lane l <-> float4 ((w * hm8 + (2*i + j) * 4 + q4) * 64 + l) of the tile's slot
+    // (the address is rebuilt where it is used, from an opaque copy of the thread index: nothing of it is
+    // carried through the main loop)
+    auto my_slot = [&]() {
+      int tp = tid;
+      asm volatile("" : "+v"(tp));
+      const size_t slot = (size_t)kWaves * p.hm8 * 64;
+      return p.part + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * slot + (size_t)(tp >> 6) * p.hm8 * 64 + (tp & 63);
+    };
+    if (p.reduce) {                                     // pass 2: start from the slices' tiles, in slice order
+      const float4* mine = my_slot();
+      const size_t slot = (size_t)kWaves * p.hm8 * 64;
+      for (int sl = 0; sl < p.kslices; ++sl) {
+        const float4* src = mine + (size_t)sl * gridDim.x * slot;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (i < NBW)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+              for (int q4 = 0; q4 < 4; ++q4) {
+                const float4 v = src[((2 * i + j) * 4 + q4) * 64];
+                acc[i][j][4 * q4] += v.x; acc[i][j][4 * q4 + 1] += v.y;
+                acc[i][j][4 * q4 + 2] += v.z; acc[i][j][4 * q4 + 3] += v.w;
+              }
+      }
+    }
 
     // Operand registers.  The token fragments are double-buffered (X[parity]); a weight fragment and
     // a weight scale are replaced in place as soon as the MFMAs that read them have been issued, one
@@ -346,6 +394,19 @@ void serq_mx_kernel(const MxParams p) {
     }
 
     // ---- epilogue ---------------------------------------------------------------
+    if (part_out) {                                     // pass 1: park the slice's tile
+      float4* mine = my_slot();
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (i < NBW)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+              mine[((2 * i + j) * 4 + q4) * 64] = make_float4(acc[i][j][4 * q4], acc[i][j][4 * q4 + 1], acc[i][j][4 * q4 + 2],
+                                                              acc[i][j][4 * q4 + 3]);
+      return;
+    }
     // register e of lane l in tile (i,j): channel n0 + 32*(blk0+i) + 8*(e/4) + 4*g + e%4,
     //                                     token   m0 + 64*wm + 32*j + lm.
     // (lane indices rebuilt from an opaque copy of the thread index: nothing of them is carried
@@ -416,6 +477,15 @@ void serq_mx_kernel(const MxParams p) {
 
 }  // namespace
 
+// bytes of workspace the sliced path needs for this call (0: not sliced); `forced` as MxLinearArgs::splitk
+size_t mx_split_workspace_bytes(int M, int N, int K, int forced) {
+  if (M <= 0) return 0;
+  const SplitPlan pl = plan_split(M, N, K, 0, device_cu_count(), forced);
+  if (pl.S <= 1) return 0;
+  const size_t tiles = (size_t)((M + BM - 1) / BM) * pl.C;
+  return (size_t)pl.S * tiles * kWaves * wave_blocks8(pl.wide) * 64 * sizeof(float4);
+}
+
 int launch_mx_linear(const MxLinearArgs& a, hipStream_t st) {
   const int ncu = device_cu_count();
   MxParams p;
@@ -425,7 +495,18 @@ int launch_mx_linear(const MxLinearArgs& a, hipStream_t st) {
   p.Y = a.Y; p.y_dtype = a.y_dtype; p.ldy = a.ldy;
   p.tiles_m = (a.M + BM - 1) / BM;
   const int NB = a.N / 32;
-  plan_columns(p.tiles_m, NB, ncu, p.tiles_n, p.wide, p.nwide);
+  // K slices need their part of the workspace (it lies behind the decode kernel's words); without it, none
+  const size_t ws_skip = skinny_mx_workspace_bytes(a.N);
+  const size_t ws_have = (a.workspace && a.workspace_bytes > ws_skip) ? a.workspace_bytes - ws_skip : 0;
+  SplitPlan pl = plan_split(a.M, a.N, a.K, 0, ncu, a.coltiles > 0 && a.splitk == 0 ? 1 : a.splitk);
+  if (pl.S > 1) {
+    const size_t need = (size_t)pl.S * p.tiles_m * pl.C * kWaves * wave_blocks8(pl.wide) * 64 * sizeof(float4);
+    if (need > ws_have) {
+      if (a.splitk > 1) return SERQ_EWORKSPACE;         // an explicit request cannot be honoured
+      pl = plan_split(a.M, a.N, a.K, 0, ncu, 1);
+    }
+  }
+  p.tiles_n = pl.C; p.wide = pl.wide; p.nwide = pl.nwide;
   if (a.coltiles > 0) {
     int C = a.coltiles < (NB + 7) / 8 ? (NB + 7) / 8 : (a.coltiles > NB ? NB : a.coltiles);
     p.tiles_n = C;
@@ -433,9 +514,18 @@ int launch_mx_linear(const MxLinearArgs& a, hipStream_t st) {
     p.nwide = NB - C * (p.wide - 1);
   }
   p.groupm = 4;
+  p.kslices = pl.S; p.reduce = 0;
+  p.hm8 = wave_blocks8(p.wide);
+  p.part = pl.S > 1 ? (float4*)((char*)a.workspace + ws_skip) : nullptr;
   const long long tiles = (long long)p.tiles_m * p.tiles_n;
   if (tiles > 0x7fffffffLL) return SERQ_ESHAPE;
-  hipLaunchKernelGGL(serq_mx_kernel, dim3((unsigned)tiles), dim3(kThreads), 0, st, p);
+  if (pl.S > 1) {
+    const size_t need = (size_t)pl.S * tiles * kWaves * p.hm8 * 64 * sizeof(float4);
+    if (need > ws_have) return SERQ_EWORKSPACE;         // (a column-tiling override can change the size)
+    hipLaunchKernelGGL(serq_mx_kernel, dim3((unsigned)tiles, (unsigned)pl.S), dim3(kThreads), 0, st, p);   // pass 1
+    p.reduce = 1;
+  }
+  hipLaunchKernelGGL(serq_mx_kernel, dim3((unsigned)tiles), dim3(kThreads), 0, st, p);   // the whole layer, or pass 2
   return hipGetLastError() == hipSuccess ? SERQ_OK : SERQ_EHIP;
 }
 

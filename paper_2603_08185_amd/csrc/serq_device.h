@@ -239,9 +239,10 @@ struct MxLinearArgs {
   int M, N, K;
   void* Y; int y_dtype; int64_t ldy;
   int coltiles;
-  int splitk;                       // decode kernel: K slices per channel block (0 = choose)
+  int splitk;                       // K slices: per channel block (decode kernel) or per tile (0 = choose, 1 = none)
   void* workspace; size_t workspace_bytes;
 };
+size_t mx_split_workspace_bytes(int M, int N, int K, int forced);
 int launch_mx_quantize_act(const void* X, const void* U, int x_dtype, const float* s_inv, int64_t M, int K, int64_t ldx,
                            int64_t ldu, void* Xq, uint8_t* xsc, hipStream_t st);
 int mx_pack_weights_impl(const void* W, int w_dtype, const float* s, const int32_t* perm, int N, int K, int r,

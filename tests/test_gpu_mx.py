@@ -12,7 +12,7 @@ import torch
 import workloads
 from oracle import serq_oracle as orc
 from paper_2603_08185_amd import binding as serq
-from tests._util import DT, assert_y_close, f32
+from tests._util import DT, assert_y_close, f32, f64
 
 pytestmark = pytest.mark.gpu
 
@@ -322,6 +322,56 @@ def test_mx_config3_M4096(which):
 @pytest.mark.parametrize("which", ["up", "down"])
 def test_mx_config3_M256(which):
     _run_mx(workloads.config3(which, 256))
+
+
+def _mx_split_ws(M, N, K, S):
+    # the decode kernel's words, then room for S parked fp32 tiles of 256 x 256 per output tile
+    n = serq.lib().serq_mx_workspace_bytes(1, N, K) + S * ((M + 255) // 256) * (N // 32) * 256 * 1024
+    ws = torch.empty(n, dtype=torch.uint8, device=DEV)
+    serq._check("serq_workspace_init", serq.lib().serq_workspace_init(serq._ptr(ws), ws.numel(), serq._stream()))
+    return ws
+
+
+# K slices of the tiled kernel (two launches: the slices park their fp32 tiles, a second pass adds them up in
+# slice order and runs the compensation tiles): forced through the flags on shapes with a partial last
+# 256-channel tile, several token tiles and several column tilings
+@pytest.mark.parametrize("out_dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("M,K,N,r,S", [(70, 832, 64, 64, 2), (300, 1088, 288, 128, 4), (256, 2048, 96, 256, 3),
+                                       (33, 4352, 544, 0, 7)])
+def test_mx_tiled_kernel_k_slices(out_dtype, M, K, N, r, S):
+    spec = _spec(M, K, N, r, out_dtype=out_dtype)
+    L = workloads.make_layer(spec, want=("X", "s", "W"))
+    pk_o = orc.mx_pack_weights(f32(L["W"]), L["s"].numpy(), r)
+    pk = serq.mx_pack_weights(L["W"].to(DEV), L["s"].to(DEV), r)
+    Xhat = workloads.permute_channels(L["X"], pk_o["perm"])
+    Xc_o, Xe_o = orc.mx_quantize_act(f32(Xhat), pk_o["s_inv"])
+    Xq, xsc = serq.mx_quantize_act(Xhat.to(DEV), pk.s_inv)
+    Y64 = orc.mx_linear(Xc_o, Xe_o, pk_o["Wc"], pk_o["We"], pk_o["Rc"] if r else None, pk_o["Re"] if r else None)
+    ws = _mx_split_ws(M, N, K, S)
+    kw = dict(Rq=pk.Rq if r else None, rsc=pk.rsc if r else None, r=r, out_dtype=DT[out_dtype])
+    Y1 = serq.mx_linear(Xq, xsc, pk.Wq, pk.wsc, M, N, K, flags_=serq.flags(serq.PATH_MFMA, splitk=1), **kw)
+    for coltiles in (0, 3, 2047):
+        fl = serq.flags(serq.PATH_MFMA, splitk=S, coltiles=coltiles)
+        Ya = serq.mx_linear(Xq, xsc, pk.Wq, pk.wsc, M, N, K, ws=ws, flags_=fl, **kw)
+        Yb = serq.mx_linear(Xq, xsc, pk.Wq, pk.wsc, M, N, K, ws=ws, flags_=fl, **kw)
+        assert torch.equal(Ya, Yb), coltiles                       # fixed order of addition
+        assert_y_close(Ya, Y64, f"{spec.name} S={S} coltiles={coltiles}")
+        # against the unsliced kernel: the same sums up to fp32 reordering (and one rounding of a 16-bit output)
+        tol = 1e-5 if out_dtype == "fp32" else 2.0 ** -7
+        assert np.max(np.abs(f64(Ya) - f64(Y1))) <= tol * np.max(np.abs(Y64)), coltiles
+    assert not ws[:serq.lib().serq_mx_workspace_bytes(1, N, K)].any()     # the decode kernel's words stay clean
+    with pytest.raises(serq.SerqError) as e:                       # an explicit request without room for it
+        serq.mx_linear(Xq, xsc, pk.Wq, pk.wsc, M, N, K, ws=None, flags_=serq.flags(serq.PATH_MFMA, splitk=S), **kw)
+    assert e.value.code == -5
+
+
+def test_mx_config3_down_M256_sliced_by_the_library():
+    # K = 11008 over 43 tiles of 256 channels, one token tile: the library cuts K when it is given the workspace
+    spec = workloads.config3("down", 256)
+    assert serq.lib().serq_mx_workspace_bytes(spec.M, spec.N, spec.K) > serq.lib().serq_mx_workspace_bytes(1, spec.N, spec.K)
+    Ya, Y64, _ = _run_mx(spec, ws=True)
+    Yb, _, _ = _run_mx(spec, ws=False)
+    assert np.max(np.abs(f64(Ya) - f64(Yb))) <= 2.0 ** -7 * np.max(np.abs(Y64))
 
 
 def test_mx_error_codes():

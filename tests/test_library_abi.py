@@ -117,7 +117,8 @@ def test_mx_and_fused_entry_points_validate_before_any_launch():
     assert L.serq_mx_weight_scale_bytes(11008, 4096) == 344 * 16 * 256
     assert L.serq_mx_weight_scale_bytes(48, 4096) == 0
     assert L.serq_mx_workspace_bytes(1, 4096, 4096) == 128 * 1024 * 4 * 17
-    assert L.serq_mx_workspace_bytes(64, 4096, 4096) == 0                # the tiled kernel takes none
+    assert L.serq_mx_workspace_bytes(4096, 4096, 4096) == 128 * 1024 * 4 * 17   # enough tiles: the tiled kernel never cuts K
+    assert L.serq_mx_workspace_bytes(64, 4096, 4096) >= 128 * 1024 * 4 * 17     # few tokens: room for parked tiles behind it
     # mx_quantize_act / the fused quantisers
     assert L.serq_mx_quantize_act(p, 7, None, 1, 64, 64, p, p, None) == -2
     assert L.serq_mx_quantize_act(p, 2, None, 1, 96, 96, p, p, None) == -3
