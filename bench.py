@@ -491,8 +491,10 @@ def sweep(only: str = ""):
             def mq(i):
                 serq.mx_quantize_act(Xhat, mpk.s_inv, Xq=Xq4, xsc=xsc)
 
+            mws2 = serq.mx_workspace(M, N, K, dev)                # K slices for few tokens and a long K
+
             def mlin(i):
-                serq.mx_linear(Xq4, xsc, mpk.Wq, mpk.wsc, M, N, K, Rq=mpk.Rq, rsc=mpk.rsc, r=rm, Y=Y)
+                serq.mx_linear(Xq4, xsc, mpk.Wq, mpk.wsc, M, N, K, Rq=mpk.Rq, rsc=mpk.rsc, r=rm, Y=Y, ws=mws2)
 
             mq(0)
             spin_up(lambda: mlin(0), 0.05)
