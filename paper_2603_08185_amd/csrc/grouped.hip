@@ -319,18 +319,24 @@ __device__ __forceinline__ void fold_tile(const GS16& gs, const v16i& acc, v16f&
 }
 
 // 8 re-centred codes (code - zero) of one lane as exact 16-bit floats; all zero for a lane without a token
+// (in two steps, so that a loop can have the loads of several fragments in flight before it converts the first)
 template <int ABITS>
-__device__ __forceinline__ u4 lr_operand(const uint8_t* xrow, int col, int zm, bool valid, bool bf) {
+__device__ __forceinline__ u2 lr_load(const uint8_t* xrow, int col) {
+  if constexpr (ABITS == 8) return *(const u2*)(xrow + col);
+  else return u2{*(const uint32_t*)(xrow + (col >> 1)), 0u};
+}
+template <int ABITS>
+__device__ __forceinline__ u4 lr_convert(const u2& x, int zm, bool valid, bool bf) {
   int c[8];
-  if constexpr (ABITS == 8) {
-    const u2 x = *(const u2*)(xrow + col);
-    codes_from_a8(x.x, x.y, c);
-  } else {
-    codes_from_a4(*(const uint32_t*)(xrow + (col >> 1)), c);
-  }
+  if constexpr (ABITS == 8) codes_from_a8(x.x, x.y, c);
+  else codes_from_a4(x.x, c);
 #pragma unroll
   for (int i = 0; i < 8; ++i) c[i] = valid ? c[i] - zm : 0;
   return codes8_to_16bit(c, bf);
+}
+template <int ABITS>
+__device__ __forceinline__ u4 lr_operand(const uint8_t* xrow, int col, int zm, bool valid, bool bf) {
+  return lr_convert<ABITS>(lr_load<ABITS>(xrow, col), zm, valid, bf);
 }
 
 __device__ __forceinline__ v16f mfma_lr16(const u4& r, const u4& x, v16f acc, bool bf) {
@@ -660,17 +666,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
   if (has_lr) {
     const int JB = p.r >> 4;
+    // four 16-rank fragments at a time: their token codes and R fragments (straight from L2) are all requested
+    // before the first is converted, so the loop pays the load latency once per four fragments
+    constexpr int NJ = 4;
 #pragma unroll 1
-    for (int jb = 0; jb < JB; ++jb) {
-      u4 xf[2];
+    for (int jb0 = 0; jb0 < JB; jb0 += NJ) {
+      u2 xr[NJ][2];
+      u4 rr[NJ][2];
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-        xf[j] = lr_operand<ABITS>(p.Xq + (size_t)mrow[j] * rowbytes, p.s_begin + 16 * jb + 8 * g, zm[j], rv[j], bf);
+      for (int q = 0; q < NJ; ++q) {
+        const int jb = jb0 + q < JB ? jb0 + q : JB - 1;   // past the end: a duplicate, never used
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const u4 rr = p.Rp[((size_t)bi[i] * JB + jb) * 64 + l];
+        for (int j = 0; j < 2; ++j) xr[q][j] = lr_load<ABITS>(p.Xq + (size_t)mrow[j] * rowbytes, p.s_begin + 16 * jb + 8 * g);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) accf[i][j] = mfma_lr16(rr, xf[j], accf[i][j], bf);
+        for (int i = 0; i < 2; ++i) rr[q][i] = p.Rp[((size_t)bi[i] * JB + jb) * 64 + l];
+      }
+#pragma unroll
+      for (int q = 0; q < NJ; ++q) {
+        if (jb0 + q < JB) {                               // uniform
+          u4 xf[2];
+#pragma unroll
+          for (int j = 0; j < 2; ++j) xf[j] = lr_convert<ABITS>(xr[q][j], zm[j], rv[j], bf);
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) accf[i][j] = mfma_lr16(rr[q][i], xf[j], accf[i][j], bf);
+        }
       }
     }
   }
