@@ -149,6 +149,8 @@ def _run(spec, path=serq.PATH_AUTO, asym=True, R_mode="residual", s_begin=0):
     (32, 1152, 288, 128, serq.PATH_SKINNY),
     (5, 640, 64, 144, serq.PATH_SKINNY),
     (17, 4096, 64, 64, serq.PATH_SKINNY),
+    (5, 8192, 64, 32, serq.PATH_SKINNY),            # long K: four groups in flight per wave
+    (25, 8320, 32, 16, serq.PATH_SKINNY),           # 65 groups: a ragged last round of them, all four register quads live
     (33, 128, 32, 16, serq.PATH_MFMA),
     (40, 384, 96, 32, serq.PATH_MFMA),
     (300, 1152, 288, 128, serq.PATH_MFMA),
@@ -199,6 +201,11 @@ def test_g128_config2_attention_projection():
                                      ("up", 4096), ("down", 4096)])
 def test_g128_config3_mlp_pair(which, M):
     _run(workloads.config3(which, M), R_mode="random")
+
+
+@pytest.mark.parametrize("M", [1, 4, 32])
+def test_g128_config4_decode(M):
+    _run(workloads.config4(M), R_mode="random")
 
 
 def test_g128_error_codes():
