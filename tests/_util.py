@@ -37,11 +37,29 @@ class OracleLayer:
     rows: Optional[np.ndarray]  # sampled token rows (None = all)
 
 
+_PACK_CACHE: dict = {}
+
+
+def oracle_pack(kind: str, spec, L) -> dict:
+    """The oracle's offline pack of a layer ('int', 'mx' or 'g128'), kept for the next test that asks for the same
+    layer: the wide decode layers are packed once for all their token counts (one entry per kind; the key holds
+    the layer's identity and a sample of its values).  Callers read the result, they do not change it."""
+    s_t = L.get("s")
+    key = (spec.cfg, spec.seed_index, spec.N, spec.K, spec.r, spec.in_dtype,
+           L["W"][0, :64].double().sum().item(), L["W"][-1, -64:].double().sum().item(),
+           None if s_t is None else s_t[:64].double().sum().item())
+    hit = _PACK_CACHE.get(kind)
+    if hit is not None and hit[0] == key:
+        return hit[1]
+    fn = {"int": orc.pack_weights, "mx": orc.mx_pack_weights, "g128": orc.pack_weights_grouped}[kind]
+    pk = fn(f32(L["W"]), s_t.numpy() if s_t is not None else None, spec.r)
+    _PACK_CACHE[kind] = (key, pk)
+    return pk
+
+
 def oracle_layer(spec, L, R_mode: str = "random", rows=None) -> OracleLayer:
     """Oracle-side preparation.  R_mode: 'random' (the drawn R), 'residual' (Eq. 5), 'none'."""
-    W = f32(L["W"])
-    s = L["s"].numpy() if L.get("s") is not None else None
-    pk = orc.pack_weights(W, s, spec.r)
+    pk = oracle_pack("int", spec, L)
     Xhat = workloads.permute_channels(L["X"], pk["perm"])
     Xs = Xhat if rows is None else Xhat[torch.as_tensor(rows)]
     Xq, scale = orc.quantize_act(f32(Xs), pk["s_inv"], spec.abits)

@@ -10,7 +10,7 @@ import torch
 import workloads
 from oracle import serq_oracle as orc
 from paper_2603_08185_amd import binding as serq
-from tests._util import DT, assert_y_close, f32, f64, ulp_close
+from tests._util import DT, assert_y_close, f32, f64, oracle_pack, ulp_close
 
 pytestmark = pytest.mark.gpu
 
@@ -114,7 +114,7 @@ def test_g128_pack_zero_groups_and_scale_range():
 def _run(spec, path=serq.PATH_AUTO, asym=True, R_mode="residual", s_begin=0):
     L = workloads.make_layer(spec)
     rdt = DT[spec.in_dtype]
-    pk_o = orc.pack_weights_grouped(f32(L["W"]), L["s"].numpy(), spec.r)
+    pk_o = oracle_pack("g128", spec, L)
     pk = serq.g128_pack_weights(L["W"].to(DEV), L["s"].to(DEV), spec.r, r_dtype=rdt)
     _check_pack(pk, pk_o, spec.N, spec.K, spec.r, rdt)
     Xhat = workloads.permute_channels(L["X"], pk_o["perm"])

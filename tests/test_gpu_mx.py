@@ -12,7 +12,7 @@ import torch
 import workloads
 from oracle import serq_oracle as orc
 from paper_2603_08185_amd import binding as serq
-from tests._util import DT, assert_y_close, f32, f64
+from tests._util import DT, assert_y_close, f32, f64, oracle_pack
 
 pytestmark = pytest.mark.gpu
 
@@ -136,7 +136,7 @@ def test_mx_pack_zero_rows_and_blocks():
 # ---------------------------------------------------------------------------
 def _run_mx(spec, rows=None, s_begin=0, with_R=True, coltiles=0, path=serq.PATH_AUTO, cols=None, ws=False, splitk=0):
     L = workloads.make_layer(spec, want=("X", "s", "W"))
-    pk_o = orc.mx_pack_weights(f32(L["W"]), L["s"].numpy(), spec.r)
+    pk_o = oracle_pack("mx", spec, L)
     pk = serq.mx_pack_weights(L["W"].to(DEV), L["s"].to(DEV), spec.r)
     _check_pack(pk, pk_o, spec.N, spec.K, spec.r)
     Xhat = workloads.permute_channels(L["X"], pk_o["perm"])
