@@ -695,6 +695,41 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       }
     }
   }
+  if (p.y_dtype != SERQ_F32) {
+    // 16-bit output: cast, transpose through LDS (the ring is free now; rows of 256 B, the 16-byte piece pc of
+    // row r at piece pc ^ (r & 15)), then stores of whole row segments: 16 lanes write 256 contiguous bytes
+    __syncthreads();                                    // every wave is done with the ring
+    const bool ybf = p.y_dtype == SERQ_BF16;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int r = 32 * (2 * wm + j) + lm;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int pc = 4 * (2 * wn + i) + q4;
+          const float y0 = sm[j] * accf[i][j][4 * q4], y1 = sm[j] * accf[i][j][4 * q4 + 1];
+          const float y2 = sm[j] * accf[i][j][4 * q4 + 2], y3 = sm[j] * accf[i][j][4 * q4 + 3];
+          u2 o;
+          if (ybf) o = u2{f32x2_to_bf16x2(y0, y1), f32x2_to_bf16x2(y2, y3)};
+          else o = u2{f32x2_to_f16x2(y0, y1), f32x2_to_f16x2(y2, y3)};
+          *(u2*)(lds + r * 256 + 16 * (pc ^ (r & 15)) + 8 * g) = o;
+        }
+      }
+    __syncthreads();
+    const int npc = 4 * nbt;                            // 16-byte pieces of a row that belong to the layer
+#pragma unroll 2
+    for (int rr = 0; rr < 128 / 16; ++rr) {
+      const int r = rr * 16 + (tid >> 4);
+      const int pc = tid & 15;
+      if (r < mrows && pc < npc) {
+        const u4 v = *(const u4*)(lds + r * 256 + 16 * (pc ^ (r & 15)));
+        *(u4*)((uint16_t*)p.Y + (size_t)(m0 + r) * p.ldy + nb0 * 32 + 8 * pc) = v;
+      }
+    }
+    return;
+  }
+  // fp32 output: 16-byte stores straight from the accumulators
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     if (2 * wn + i >= nbt) continue;
