@@ -541,7 +541,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const uint8_t* wbase = (const uint8_t*)p.Wq + (size_t)nb0 * KB * 1024;
   const uint8_t* xbase = p.Xq + (size_t)m0 * rowbytes;
   const uint8_t* sbase = (const uint8_t*)p.gsc + (size_t)nb0 * G * 64;
-  auto issue = [&](int gi, int st) {
+  // The sequence of stages: the G groups of the layer, then -- for the rank-r term -- once more the LG groups whose
+  // token codes are the salient block (only their token rows are read then; the loads are the same so that every
+  // stage counts the same number of them).
+  const bool has_lr = p.r > 0 && p.Rp != nullptr;
+  const int lg0 = p.s_begin >> 7;
+  const int LG = has_lr ? ((p.s_begin + p.r + 127) >> 7) - lg0 : 0;
+  const int GT = G + LG;
+  auto issue = [&](int q, int st) {
+    const int gi = q < G ? q : lg0 + (q - G);
     const uint32_t sb = lds0 + (uint32_t)st * T::STAGE;
 #pragma unroll
     for (int i = 0; i < 2; ++i) dma16(wbase + (size_t)gi * 2048, wv[i], sb + 1024 * wu + 4096 * i);
@@ -592,16 +600,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   };
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s)
-    if (s < G) issue(s, s);
+    if (s < GT) issue(s, s);
   int st = 0, sti = NS - 1;
 #pragma unroll 1
   for (int gi = 0; gi < G; ++gi) {
     // group gi has landed (this wave's loads: all but those of the NS-2 groups behind it), every wave has
     // got here, so everybody's loads have landed and the stage read last round may be refilled
-    const int last = gi + NS - 2 < G - 1 ? gi + NS - 2 : G - 1;
+    const int last = gi + NS - 2 < GT - 1 ? gi + NS - 2 : GT - 1;
     if (last - gi == NS - 2) wait_dma_barrier<(NS - 2) * T::NL>();
     else wait_dma_barrier<0>();
-    if (gi + NS - 1 < G) issue(gi + NS - 1, sti);
+    if (gi + NS - 1 < GT) issue(gi + NS - 1, sti);
     sti = sti + 1 == NS ? 0 : sti + 1;
     const uint8_t* s = lds + st * T::STAGE;
     st = st + 1 == NS ? 0 : st + 1;
@@ -638,7 +646,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   fold_tile(gprev, acc[1][1], accf[1][1]);
 
   // ---- epilogue: zero point, rank-r term on the re-centred codes, token scale, one store ----------------
-  const bool has_lr = p.r > 0 && p.Rp != nullptr;
   const bool bf = p.r_dtype == SERQ_BF16;
   int mrow[2], zm[2];
   float sm[2];
@@ -665,32 +672,55 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       for (int e = 0; e < 16; ++e) accf[i][j][e] = __builtin_fmaf(accf[i][j][e], kInv, -(float)zm[j] * ws[e]);   // 2^-SH: exact
   }
   if (has_lr) {
+    // The token codes of the salient block come back through the ring (they ran ahead of the last main groups,
+    // like any stage); the R fragments come straight from L2, four 16-rank fragments requested before the first
+    // is used.
     const int JB = p.r >> 4;
-    // four 16-rank fragments at a time: their token codes and R fragments (straight from L2) are all requested
-    // before the first is converted, so the loop pays the load latency once per four fragments
     constexpr int NJ = 4;
 #pragma unroll 1
-    for (int jb0 = 0; jb0 < JB; jb0 += NJ) {
-      u2 xr[NJ][2];
-      u4 rr[NJ][2];
+    for (int lg = 0; lg < LG; ++lg) {
+      const int q = G + lg;
+      const int last = q + NS - 2 < GT - 1 ? q + NS - 2 : GT - 1;
+      if (last - q == NS - 2) wait_dma_barrier<(NS - 2) * T::NL>();
+      else wait_dma_barrier<0>();
+      if (q + NS - 1 < GT) issue(q + NS - 1, sti);
+      sti = sti + 1 == NS ? 0 : sti + 1;
+      const uint8_t* s = lds + st * T::STAGE;
+      st = st + 1 == NS ? 0 : st + 1;
+      const int c0 = 128 * (lg0 + lg);                    // first channel of this group of token codes
+      const int jb_lo = c0 > p.s_begin ? (c0 - p.s_begin) >> 4 : 0;
+      const int jb_end = (c0 + 128 - p.s_begin) >> 4;
+      const int jb_hi = jb_end < JB ? jb_end : JB;
+#pragma unroll 1
+      for (int jb0 = jb_lo; jb0 < jb_hi; jb0 += NJ) {
+        u4 rr[NJ][2];
 #pragma unroll
-      for (int q = 0; q < NJ; ++q) {
-        const int jb = jb0 + q < JB ? jb0 + q : JB - 1;   // past the end: a duplicate, never used
+        for (int q4 = 0; q4 < NJ; ++q4) {
+          const int jb = jb0 + q4 < jb_hi ? jb0 + q4 : jb_hi - 1;   // past the end: a duplicate, never used
 #pragma unroll
-        for (int j = 0; j < 2; ++j) xr[q][j] = lr_load<ABITS>(p.Xq + (size_t)mrow[j] * rowbytes, p.s_begin + 16 * jb + 8 * g);
+          for (int i = 0; i < 2; ++i) rr[q4][i] = p.Rp[((size_t)bi[i] * JB + jb) * 64 + l];
+        }
 #pragma unroll
-        for (int i = 0; i < 2; ++i) rr[q][i] = p.Rp[((size_t)bi[i] * JB + jb) * 64 + l];
-      }
+        for (int q4 = 0; q4 < NJ; ++q4) {
+          if (jb0 + q4 < jb_hi) {                         // uniform
+            const int col = p.s_begin + 16 * (jb0 + q4) + 8 * g - c0;   // this lane's first channel within the group
+            u4 xf[2];
 #pragma unroll
-      for (int q = 0; q < NJ; ++q) {
-        if (jb0 + q < JB) {                               // uniform
-          u4 xf[2];
+            for (int j = 0; j < 2; ++j) {
+              u2 xr;
+              if constexpr (ABITS == 8) {
+                xr = *(const u2*)(s + xoff[j] + 16 * ((col >> 4) ^ xsw[j]) + (col & 15));
+              } else {
+                const int byte = col >> 1;
+                xr = u2{*(const uint32_t*)(s + xoff[j] + 16 * ((byte >> 4) ^ xsw[j]) + (byte & 15)), 0u};
+              }
+              xf[j] = lr_convert<ABITS>(xr, zm[j], rv[j], bf);
+            }
 #pragma unroll
-          for (int j = 0; j < 2; ++j) xf[j] = lr_convert<ABITS>(xr[q][j], zm[j], rv[j], bf);
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
-          for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) accf[i][j] = mfma_lr16(rr[q][i], xf[j], accf[i][j], bf);
+              for (int j = 0; j < 2; ++j) accf[i][j] = mfma_lr16(rr[q4][i], xf[j], accf[i][j], bf);
+          }
         }
       }
     }
