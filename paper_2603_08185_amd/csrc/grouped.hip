@@ -334,6 +334,42 @@ __device__ __forceinline__ u4 lr_convert(const u2& x, int zm, bool valid, bool b
   for (int i = 0; i < 8; ++i) c[i] = valid ? c[i] - zm : 0;
   return codes8_to_16bit(c, bf);
 }
+// The same for a lane that always has a token (or a duplicate of one whose results are never stored: the columns
+// of the MFMA are independent), in fewer vector operations: the codes are turned into unsigned bytes by flipping
+// their sign bit, converted straight from the packed bytes, and re-centred by one subtraction (zero + the flipped
+// bit's worth).  |code - zero| <= 255, so the fp32 values are whole numbers that both 16-bit formats hold exactly.
+template <int ABITS>
+__device__ __forceinline__ u4 lr_convert_packed(const u2& x, int zm, bool bf) {
+  float f[8];
+  if constexpr (ABITS == 8) {
+    const uint32_t t0 = x.x ^ 0x80808080u, t1 = x.y ^ 0x80808080u;
+    const float off = (float)(128 + zm);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      f[k] = (float)((t0 >> (8 * k)) & 0xffu) - off;
+      f[4 + k] = (float)((t1 >> (8 * k)) & 0xffu) - off;
+    }
+  } else {
+    // byte j of the dword: code j in the low nibble, code 4 + j in the high nibble
+    const uint32_t t = x.x ^ 0x88888888u;
+    const uint32_t lo = t & 0x0f0f0f0fu, hi = (t >> 4) & 0x0f0f0f0fu;
+    const float off = (float)(8 + zm);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      f[k] = (float)((lo >> (8 * k)) & 0xffu) - off;
+      f[4 + k] = (float)((hi >> (8 * k)) & 0xffu) - off;
+    }
+  }
+  u4 o;
+  if (bf) {
+    o.x = f32x2_to_bf16x2(f[0], f[1]); o.y = f32x2_to_bf16x2(f[2], f[3]);
+    o.z = f32x2_to_bf16x2(f[4], f[5]); o.w = f32x2_to_bf16x2(f[6], f[7]);
+  } else {
+    o.x = f32x2_to_f16x2(f[0], f[1]); o.y = f32x2_to_f16x2(f[2], f[3]);
+    o.z = f32x2_to_f16x2(f[4], f[5]); o.w = f32x2_to_f16x2(f[6], f[7]);
+  }
+  return o;
+}
 template <int ABITS>
 __device__ __forceinline__ u4 lr_operand(const uint8_t* xrow, int col, int zm, bool valid, bool bf) {
   return lr_convert<ABITS>(lr_load<ABITS>(xrow, col), zm, valid, bf);
@@ -714,7 +750,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 const int byte = col >> 1;
                 xr = u2{*(const uint32_t*)(s + xoff[j] + 16 * ((byte >> 4) ^ xsw[j]) + (byte & 15)), 0u};
               }
-              xf[j] = lr_convert<ABITS>(xr, zm[j], rv[j], bf);
+              xf[j] = lr_convert_packed<ABITS>(xr, zm[j], bf);   // rows past M: duplicates, never stored
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
